@@ -1,0 +1,89 @@
+/* Raw kernel launchers of libdssp (layer L0): one extern "C" function per kernel family,
+ * plain device pointers and sizes, a hipStream_t passed as void*.  They enqueue and return
+ * the HIP error code of the launch (0 = success, -1 = shape not supported).  The library's
+ * own worker step is built from exactly these; they are exported so that each kernel can be
+ * checked on its own.  Every operation is a step of Alg. 1: the worker's mini-batch gradient
+ * (worker step 4) or the server's weight update (server step 2) / the worker's pull (worker
+ * steps 2-3).
+ *
+ * Layouts: activations [N][H][W][C] fp32, filters [KH][KW][Cin][Cout], FC weights [in][out].
+ */
+#ifndef DSSP_KERNELS_H
+#define DSSP_KERNELS_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Server step 2: w[i] -= scale * g[i], i < n; *stamp_dev = version. */
+int dsspk_apply(void* stream, float* w_dev, const float* g_dev, int64_t n, float scale,
+                uint64_t* stamp_dev, uint64_t version);
+/* Worker steps 2-3: dst[i] = w[i]; *dst_stamp_dev = *stamp_dev. */
+int dsspk_pull(void* stream, float* dst_dev, const float* w_dev, int64_t n,
+               uint64_t* dst_stamp_dev, const uint64_t* stamp_dev);
+
+/* C[M][N] = op(A)[M][K] * op(B)[K][N] (+ bias[N]) (ReLU if relu).  Element (i,k) of op(A) is
+ * A[i*a_rs + k*a_cs], element (k,j) of op(B) is B[k*b_rs + j*b_cs]; C is row-major with
+ * leading dimension ldc.  bias_dev may be NULL. */
+int dsspk_gemm(void* stream, const float* A_dev, long a_rs, long a_cs, const float* B_dev, long b_rs, long b_cs,
+               float* C_dev, long ldc, int M, int N, int K, const float* bias_dev, int relu);
+/* out[j] = sum_i X[i][j], X is [M][N] row-major.  Fixed summation order. */
+int dsspk_colsum(void* stream, const float* X_dev, float* out_dev, long M, int N);
+
+/* Convolution (cross-correlation, zero padding), implicit GEMM on fp32 MFMA.
+ * Ho = (H + 2*pad - KH)/stride + 1.  bias_dev may be NULL; relu applies max(.,0) to the output. */
+int dsspk_conv_fwd(void* stream, const float* x_dev, const float* w_dev, const float* bias_dev, float* y_dev,
+                   int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad, int relu);
+/* dx = transpose of the above applied to dy (gradient w.r.t. the input). */
+int dsspk_conv_bwd_data(void* stream, const float* dy_dev, const float* w_dev, float* dx_dev,
+                        int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad);
+/* dw[kh][kw][ci][co] = sum over batch and output pixels of x * dy.  Two stages (partial sums per
+ * pixel chunk, then a fixed-order reduction).  scratch_dev: dsspk_conv_wgrad_scratch_floats(...) floats. */
+int dsspk_conv_bwd_weight(void* stream, const float* x_dev, const float* dy_dev, float* dw_dev, float* scratch_dev,
+                          int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad);
+size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad);
+
+/* dy[i] = a[i] > 0 ? dy[i] : 0 (in place). */
+int dsspk_relu_bwd(void* stream, float* dy_dev, const float* a_dev, long n);
+/* out[i] += in[i]. */
+int dsspk_add(void* stream, float* out_dev, const float* in_dev, long n);
+
+/* Max pooling 3x3 stride 2, no padding, floor.  arg: chosen window position kh*3+kw (first
+ * maximum in scan order). */
+int dsspk_maxpool_fwd(void* stream, const float* x_dev, float* y_dev, uint8_t* arg_dev, int N, int H, int W, int C);
+int dsspk_maxpool_bwd(void* stream, const float* dy_dev, const uint8_t* arg_dev, float* dx_dev, int N, int H, int W, int C);
+
+/* Batch normalisation over the M rows of x[M][C], batch statistics, biased variance, eps inside
+ * the root.  stats: mean[C] then invstd[C] (written by fwd, read by bwd).
+ * fwd: y = gamma*(x-mean)*invstd + beta (+ shortcut) (ReLU if relu).
+ *   shortcut_mode 0: none; 1: sc_dev has y's shape; 2: sc_dev is [N][2Ho][2Wo][C/2], subsampled by
+ *   2 in h and w, channels >= C/2 read as zero (Ho, Wo, N given by sc_n, sc_ho, sc_wo).
+ * scratch_dev: dsspk_bn_scratch_floats(M, C) floats. */
+int dsspk_bn_fwd(void* stream, const float* x_dev, const float* gamma_dev, const float* beta_dev, float* y_dev,
+                 float* stats_dev, float* scratch_dev, long M, int C, float eps, int relu,
+                 int shortcut_mode, const float* sc_dev, int sc_n, int sc_ho, int sc_wo);
+/* Backward of ReLU(BN(x) [+ shortcut]) w.r.t. x, gamma, beta.
+ *   da_dev    gradient w.r.t. the (post-ReLU) output; overwritten IN PLACE by dz = da * [out > 0]
+ *             when out_dev != NULL (out_dev = the saved forward output), left as is otherwise
+ *   dx_dev    gamma*invstd*(dz - mean(dz) - xhat*mean(dz*xhat)) */
+int dsspk_bn_bwd(void* stream, const float* x_dev, const float* gamma_dev, const float* stats_dev,
+                 float* da_dev, const float* out_dev, float* dx_dev, float* dgamma_dev, float* dbeta_dev,
+                 float* scratch_dev, long M, int C);
+size_t dsspk_bn_scratch_floats(long M, int C);
+
+/* dx[n][2ho][2wo][c] += dy[n][ho][wo][c] for c < C/2 (transpose of shortcut_mode 2). */
+int dsspk_shortcut_bwd_acc(void* stream, const float* dy_dev, float* dx_dev, int N, int Ho, int Wo, int C);
+
+/* y[n][c] = mean over hw of x[n][hw][c];  dx[n][hw][c] = dy[n][c] / HW. */
+int dsspk_gap_fwd(void* stream, const float* x_dev, float* y_dev, int N, int HW, int C);
+int dsspk_gap_bwd(void* stream, const float* dy_dev, float* dx_dev, int N, int HW, int C);
+
+/* loss = mean_i(logsumexp(z_i) - z_i[y_i]); dz = (softmax(z) - onehot(y)) / m.  loss_dev may be NULL.
+ * m <= 1024, C <= 1024. */
+int dsspk_softmax_xent(void* stream, const float* z_dev, const int32_t* y_dev, float* dz_dev, float* loss_dev, int m, int C);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

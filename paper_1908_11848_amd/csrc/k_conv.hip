@@ -1,0 +1,388 @@
+// Convolution forward, gradient w.r.t. the input and gradient w.r.t. the filter, as implicit
+// GEMMs on the fp32 matrix cores (the dense contractions of Alg. 1's worker gradient).
+//
+//   forward : y[pixel][co]  = sum_{tap,ci} x[src(pixel,tap)][ci] * w[tap][ci][co]
+//   d-input : dx[pixel][ci] = sum_{tap,co} dy[src'(pixel,tap)][co] * w[tap][ci][co]
+//   d-filter: dw[tap][ci][co] = sum_{pixel} x[src(pixel,tap)][ci] * dy[pixel][co]
+//
+// Activations are [N][H][W][C]: the C values of a pixel are contiguous, so a k-chunk of 16
+// channels of one filter tap is one 64-byte run per pixel and neighbouring pixels of an image
+// row are neighbouring runs.  A workgroup of 4 wavefronts stages a BM-pixel x 16 slice of the
+// gathered operand and the matching 16 x C slice of the filter in LDS (double buffered, next
+// slice prefetched into registers while the matrix cores work on the current one).
+#include "mma.hpp"
+#include "../../include/dssp_kernels.h"
+
+namespace {
+
+constexpr int THREADS = 256;
+
+struct ConvGeom {
+    int N, OH, OW;      // pixel grid of the GEMM's rows
+    int SH, SW;         // spatial size of the gathered tensor
+    int IC, OC;         // channels of the gathered tensor (reduction) / of the result (columns)
+    int KH, KW, stride, pad;
+    long M;             // N * OH * OW
+};
+
+// Source pixel of row-pixel (oh, ow) for filter tap (kh, kw); false if it falls into the padding
+// (forward) or between the strides (d-input).
+template <bool DGRAD>
+__device__ __forceinline__ bool src_pixel(const ConvGeom& g, int oh, int ow, int kh, int kw, int& sh, int& sw) {
+    if constexpr (!DGRAD) {
+        sh = oh * g.stride + kh - g.pad;
+        sw = ow * g.stride + kw - g.pad;
+        return sh >= 0 && sh < g.SH && sw >= 0 && sw < g.SW;
+    } else {
+        const int hs = oh + g.pad - kh, ws = ow + g.pad - kw;
+        if (hs < 0 || ws < 0) return false;
+        if (g.stride == 1) { sh = hs; sw = ws; }
+        else {
+            if ((hs % g.stride) | (ws % g.stride)) return false;
+            sh = hs / g.stride; sw = ws / g.stride;
+        }
+        return sh < g.SH && sw < g.SW;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward / d-input.  BM rows (pixels) x BN columns per workgroup, BN = OC (16, 32 or 64; wider
+// results take several column tiles).  wavefront w owns rows [w*BM/4, (w+1)*BM/4).
+//   DGRAD: gather from dy and use the filter transposed.
+//   VEC  : IC is a multiple of 16 (one k-chunk = 16 channels of one tap, 16-byte loads);
+//          otherwise the reduction index (tap, ci) is flattened and loaded element-wise.
+template <int BM, int BN, bool DGRAD, bool VEC>
+__global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
+                                                             const float* __restrict__ bias, float* __restrict__ dst,
+                                                             ConvGeom g, int relu) {
+    constexpr int WM = BM / 64, WN = BN / 16;
+    constexpr int LDB = DGRAD ? mma::LDK : BN + 4;
+    constexpr int BS = DGRAD ? BN * mma::LDK : mma::KC * (BN + 4);
+    constexpr int RPT = BM / 64;                                   // gathered rows per thread (VEC)
+    __shared__ __attribute__((aligned(16))) float As[2][BM * mma::LDK];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long m0 = (long)blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int taps = g.KH * g.KW;
+
+    floatx4 acc[WM][WN];
+    mma::zero(acc);
+
+    // per-thread rows of the gathered tile
+    int rn[VEC ? RPT : 1], roh[VEC ? RPT : 1], row_w[VEC ? RPT : 1];
+    bool rvalid[VEC ? RPT : 1];
+    const int part = tid & 3;                                      // which float4 of the 16-channel chunk
+    if constexpr (VEC) {
+#pragma unroll
+        for (int e = 0; e < RPT; ++e) {
+            const long m = m0 + (tid >> 2) + 64 * e;
+            rvalid[e] = m < g.M;
+            const long mm = rvalid[e] ? m : 0;
+            row_w[e] = (int)(mm % g.OW);
+            roh[e] = (int)((mm / g.OW) % g.OH);
+            rn[e] = (int)(mm / ((long)g.OW * g.OH));
+        }
+    }
+
+    float4 ra[VEC ? RPT : 1];
+    float ras[VEC ? 1 : BM * mma::KC / THREADS];
+    float4 rb = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int ktot = taps * g.IC;
+    const int nchunks = VEC ? taps * (g.IC / mma::KC) : (ktot + mma::KC - 1) / mma::KC;
+
+    auto load = [&](int chunk) {
+        if constexpr (VEC) {
+            const int cpt = g.IC / mma::KC;
+            const int tap = chunk / cpt, c0 = (chunk - tap * cpt) * mma::KC;
+            const int kh = tap / g.KW, kw = tap - kh * g.KW;
+#pragma unroll
+            for (int e = 0; e < RPT; ++e) {
+                int sh, sw;
+                const bool ok = rvalid[e] && src_pixel<DGRAD>(g, roh[e], row_w[e], kh, kw, sh, sw);
+                ra[e] = ok ? *reinterpret_cast<const float4*>(src + (((long)rn[e] * g.SH + sh) * g.SW + sw) * g.IC + c0 + 4 * part)
+                           : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            if (tid < 4 * BN) {
+                if constexpr (!DGRAD) {       // rows k = channel c0+k of this tap, BN columns
+                    const int k = tid / (BN / 4), j4 = tid % (BN / 4);
+                    rb = *reinterpret_cast<const float4*>(wgt + ((long)tap * g.IC + c0 + k) * g.OC + n0 + 4 * j4);
+                } else {                      // rows j = result channel, 16 contiguous reduction channels
+                    const int j = tid >> 2;
+                    rb = *reinterpret_cast<const float4*>(wgt + ((long)tap * g.OC + n0 + j) * g.IC + c0 + 4 * part);
+                }
+            }
+        } else {
+            const int k0 = chunk * mma::KC;
+#pragma unroll
+            for (int e = 0; e < BM * mma::KC / THREADS; ++e) {
+                const int idx = tid + e * THREADS;
+                const int row = idx / mma::KC, k = idx % mma::KC;
+                const long m = m0 + row;
+                const int kk = k0 + k;
+                float v = 0.f;
+                if (m < g.M && kk < ktot) {
+                    const int tap = kk / g.IC, ci = kk - tap * g.IC;
+                    const int kh = tap / g.KW, kw = tap - kh * g.KW;
+                    const int ow = (int)(m % g.OW), oh = (int)((m / g.OW) % g.OH), n = (int)(m / ((long)g.OW * g.OH));
+                    int sh, sw;
+                    if (src_pixel<DGRAD>(g, oh, ow, kh, kw, sh, sw))
+                        v = src[(((long)n * g.SH + sh) * g.SW + sw) * g.IC + ci];
+                }
+                ras[e] = v;
+            }
+            if (tid < 4 * BN) {               // forward only: filter rows are the flattened (tap, ci)
+                const int k = tid / (BN / 4), j4 = tid % (BN / 4);
+                rb = (k0 + k < ktot) ? *reinterpret_cast<const float4*>(wgt + (long)(k0 + k) * g.OC + n0 + 4 * j4)
+                                     : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    };
+    auto store = [&](int buf) {
+        if constexpr (VEC) {
+#pragma unroll
+            for (int e = 0; e < RPT; ++e)
+                *reinterpret_cast<float4*>(&As[buf][((tid >> 2) + 64 * e) * mma::LDK + 4 * part]) = ra[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < BM * mma::KC / THREADS; ++e) {
+                const int idx = tid + e * THREADS;
+                As[buf][(idx / mma::KC) * mma::LDK + idx % mma::KC] = ras[e];
+            }
+        }
+        if (tid < 4 * BN) {
+            if constexpr (!DGRAD) {
+                const int k = tid / (BN / 4), j4 = tid % (BN / 4);
+                *reinterpret_cast<float4*>(&Bs[buf][k * LDB + 4 * j4]) = rb;
+            } else {
+                *reinterpret_cast<float4*>(&Bs[buf][(tid >> 2) * LDB + 4 * part]) = rb;
+            }
+        }
+    };
+
+    load(0);
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        store(buf);
+        __syncthreads();
+        if (c + 1 < nchunks) load(c + 1);
+        mma::chunk16<WM, WN, false, DGRAD>(As[buf], mma::LDK, Bs[buf], LDB, wave * (BM / 4), 0, acc, lane);
+    }
+
+    const int l16 = lane & 15, q = lane >> 4;
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) {
+            const int col = n0 + 16 * wn + l16;
+            const float bv = bias ? bias[col] : 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const long m = m0 + wave * (BM / 4) + 16 * wm + 4 * q + v;
+                if (m >= g.M) continue;
+                float x = acc[wm][wn][v] + bv;
+                if (relu) x = fmaxf(x, 0.f);
+                dst[m * g.OC + col] = x;
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// d-filter, stage 1.  Workgroup (chunk, tap) reduces `stages` slices of 64 output pixels for one
+// filter tap and writes a partial [CIP][COP] block; wavefront w takes pixels [16w, 16w+16) of
+// every slice, the four wavefronts' tiles are summed in a fixed order at the end.
+//   VEC  : Cin is a multiple of 16, rows of the tile are the channels of tap blockIdx.y.
+//   !VEC : rows are the flattened (tap, ci) index (first layer, Cin = 3), blockIdx.y = 0.
+template <int CI_T, int CO_T, bool VEC>
+__global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                             float* __restrict__ partial, ConvGeom g, int stages, int rows_total) {
+    constexpr int CIP = 16 * CI_T, COP = 16 * CO_T;
+    constexpr int LDA = CIP + 4, LDB = COP + 4;
+    constexpr int PIX = 64;
+    __shared__ __attribute__((aligned(16))) float Xs[PIX * LDA];
+    __shared__ __attribute__((aligned(16))) float Ds[PIX * LDB];
+    __shared__ __attribute__((aligned(16))) float Red[CIP * COP];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tap = blockIdx.y;
+    const int kh = tap / g.KW, kw = tap - kh * g.KW;
+    const long p_begin = (long)blockIdx.x * stages * PIX;
+
+    floatx4 acc[CI_T][CO_T];
+    mma::zero(acc);
+
+    for (int st = 0; st < stages; ++st) {
+        const long p0 = p_begin + (long)st * PIX;
+        if (p0 >= g.M) break;
+        __syncthreads();                                            // previous slice fully consumed
+        if constexpr (VEC) {
+            for (int idx = tid; idx < PIX * (CIP / 4); idx += THREADS) {
+                const int pix = idx / (CIP / 4), c4 = idx % (CIP / 4);
+                const long m = p0 + pix;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (m < g.M) {
+                    const int ow = (int)(m % g.OW), oh = (int)((m / g.OW) % g.OH), n = (int)(m / ((long)g.OW * g.OH));
+                    int sh, sw;
+                    if (src_pixel<false>(g, oh, ow, kh, kw, sh, sw))
+                        v = *reinterpret_cast<const float4*>(x + (((long)n * g.SH + sh) * g.SW + sw) * g.IC + 4 * c4);
+                }
+                *reinterpret_cast<float4*>(&Xs[pix * LDA + 4 * c4]) = v;
+            }
+        } else {
+            for (int idx = tid; idx < PIX * CIP; idx += THREADS) {
+                const int pix = idx / CIP, kk = idx % CIP;
+                const long m = p0 + pix;
+                float v = 0.f;
+                if (m < g.M && kk < rows_total) {
+                    const int t2 = kk / g.IC, ci = kk - t2 * g.IC;
+                    const int kh2 = t2 / g.KW, kw2 = t2 - kh2 * g.KW;
+                    const int ow = (int)(m % g.OW), oh = (int)((m / g.OW) % g.OH), n = (int)(m / ((long)g.OW * g.OH));
+                    int sh, sw;
+                    if (src_pixel<false>(g, oh, ow, kh2, kw2, sh, sw))
+                        v = x[(((long)n * g.SH + sh) * g.SW + sw) * g.IC + ci];
+                }
+                Xs[pix * LDA + kk] = v;
+            }
+        }
+        for (int idx = tid; idx < PIX * (COP / 4); idx += THREADS) {
+            const int pix = idx / (COP / 4), c4 = idx % (COP / 4);
+            const long m = p0 + pix;
+            const float4 v = m < g.M ? *reinterpret_cast<const float4*>(dy + m * g.OC + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            *reinterpret_cast<float4*>(&Ds[pix * LDB + 4 * c4]) = v;
+        }
+        __syncthreads();
+        mma::chunk16<CI_T, CO_T, true, false>(Xs + 16 * wave * LDA, LDA, Ds + 16 * wave * LDB, LDB, 0, 0, acc, lane);
+    }
+
+    // ((w0 + w1) + w2) + w3, element by element
+    const int l16 = lane & 15, q = lane >> 4;
+    for (int w = 0; w < 4; ++w) {
+        __syncthreads();
+        if (wave == w) {
+#pragma unroll
+            for (int a = 0; a < CI_T; ++a)
+#pragma unroll
+                for (int b = 0; b < CO_T; ++b)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int idx = (16 * a + 4 * q + v) * COP + 16 * b + l16;
+                        Red[idx] = (w == 0 ? 0.f : Red[idx]) + acc[a][b][v];
+                    }
+        }
+    }
+    __syncthreads();
+    // partial[chunk][row][co]; VEC: row = tap*Cin + ci, else row = flattened (tap, ci)
+    const int rows = VEC ? g.IC : rows_total;
+    float* out = partial + ((long)blockIdx.x * rows_total + (VEC ? (long)tap * g.IC : 0)) * g.OC;
+    for (int idx = tid; idx < rows * g.OC; idx += THREADS) {
+        const int rr = idx / g.OC, co = idx - rr * g.OC;
+        out[idx] = Red[rr * COP + co];
+    }
+}
+
+// d-filter, stage 2: dw[e] = sum over chunks of partial[chunk][e], chunks in ascending order
+// within each of 8 interleaved groups, groups combined pairwise in a fixed order.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dw,
+                                                           int E, int chunks) {
+    __shared__ float part[8][32];
+    const int c = threadIdx.x & 31, gq = threadIdx.x >> 5;
+    const int e = blockIdx.x * 32 + c;
+    float s = 0.f;
+    if (e < E)
+        for (int k = gq; k < chunks; k += 8) s += partial[(long)k * E + e];
+    part[gq][c] = s;
+    __syncthreads();
+    if (gq == 0 && e < E)
+        dw[e] = ((part[0][c] + part[1][c]) + (part[2][c] + part[3][c])) + ((part[4][c] + part[5][c]) + (part[6][c] + part[7][c]));
+}
+
+bool geom(ConvGeom& g, int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
+    if (N < 1 || H < 1 || W < 1 || Cin < 1 || Cout < 1 || KH < 1 || KW < 1 || stride < 1 || pad < 0) return false;
+    if (H + 2 * pad < KH || W + 2 * pad < KW) return false;
+    g.N = N; g.KH = KH; g.KW = KW; g.stride = stride; g.pad = pad;
+    g.SH = H; g.SW = W; g.IC = Cin; g.OC = Cout;
+    g.OH = (H + 2 * pad - KH) / stride + 1;
+    g.OW = (W + 2 * pad - KW) / stride + 1;
+    g.M = (long)N * g.OH * g.OW;
+    return true;
+}
+
+int wgrad_stages(const ConvGeom& g, int grid_y) {
+    long s = g.M * grid_y / (64L * 128L);
+    if (s < 1) s = 1;
+    if (s > 16) s = 16;
+    return (int)s;
+}
+
+template <bool DGRAD, bool VEC>
+int launch_igemm(hipStream_t s, const float* src, const float* w, const float* bias, float* dst, const ConvGeom& g, int relu) {
+    const int bn = g.OC >= 64 ? 64 : g.OC;
+    if (bn != 16 && bn != 32 && bn != 64) return -1;
+    if (g.OC % bn) return -1;
+    // small problems take 64-pixel tiles so that the grid still covers the chip
+    const bool small = g.M < 128L * 512;
+    dim3 grid(ceil_div(g.M, small ? 64 : 128), g.OC / bn);
+#define GO(BM, BN) hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, DGRAD, VEC>), grid, dim3(THREADS), 0, s, src, w, bias, dst, g, relu)
+    if (small) { if (bn == 16) GO(64, 16); else if (bn == 32) GO(64, 32); else GO(64, 64); }
+    else       { if (bn == 16) GO(128, 16); else if (bn == 32) GO(128, 32); else GO(128, 64); }
+#undef GO
+    return DSSPK_LAUNCH_RC();
+}
+
+}  // namespace
+
+extern "C" int dsspk_conv_fwd(void* stream, const float* x, const float* w, const float* bias, float* y,
+                              int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad, int relu) {
+    ConvGeom g;
+    if (!x || !w || !y || !geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
+    if (Cin % 16 == 0) return launch_igemm<false, true>((hipStream_t)stream, x, w, bias, y, g, relu);
+    return launch_igemm<false, false>((hipStream_t)stream, x, w, bias, y, g, relu);
+}
+
+extern "C" int dsspk_conv_bwd_data(void* stream, const float* dy, const float* w, float* dx,
+                                   int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
+    ConvGeom f;
+    if (!dy || !w || !dx || !geom(f, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
+    if (Cout % 16) return -1;
+    ConvGeom g = f;                       // rows: input pixels; gathered tensor: dy
+    g.OH = H; g.OW = W; g.SH = f.OH; g.SW = f.OW; g.IC = Cout; g.OC = Cin;
+    g.M = (long)N * H * W;
+    return launch_igemm<true, true>((hipStream_t)stream, dy, w, nullptr, dx, g, 0);
+}
+
+extern "C" size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
+    ConvGeom g;
+    if (!geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return 0;
+    const int gy = (Cin % 16 == 0) ? KH * KW : 1;
+    const int stages = wgrad_stages(g, gy);
+    const long chunks = ceil_div(g.M, 64L * stages);
+    return (size_t)chunks * KH * KW * Cin * Cout;
+}
+
+extern "C" int dsspk_conv_bwd_weight(void* stream, const float* x, const float* dy, float* dw, float* scratch,
+                                     int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
+    ConvGeom g;
+    if (!x || !dy || !dw || !scratch || !geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
+    if (Cout != 16 && Cout != 32 && Cout != 64) return -1;
+    hipStream_t s = (hipStream_t)stream;
+    const bool vec = Cin % 16 == 0;
+    const int rows_total = KH * KW * Cin;
+    const int gy = vec ? KH * KW : 1;
+    const int stages = wgrad_stages(g, gy);
+    const int chunks = ceil_div(g.M, 64L * stages);
+    dim3 grid(chunks, gy);
+#define GO(CI, CO, V) hipLaunchKernelGGL((conv_wgrad_kernel<CI, CO, V>), grid, dim3(THREADS), 0, s, x, dy, scratch, g, stages, rows_total)
+#define GO_CO(CI, V) do { if (Cout == 16) GO(CI, 1, V); else if (Cout == 32) GO(CI, 2, V); else GO(CI, 4, V); } while (0)
+    if (vec) {
+        if (Cin == 16) GO_CO(1, true); else if (Cin == 32) GO_CO(2, true); else if (Cin == 64) GO_CO(4, true); else return -1;
+    } else {
+        const int tiles = ceil_div(rows_total, 16);
+        if (tiles <= 2) GO_CO(2, false); else if (tiles <= 5) GO_CO(5, false); else return -1;
+    }
+#undef GO_CO
+#undef GO
+    int rc = DSSPK_LAUNCH_RC();
+    if (rc) return rc;
+    const int E = rows_total * Cout;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(ceil_div(E, 32)), dim3(256), 0, s, scratch, dw, E, chunks);
+    return DSSPK_LAUNCH_RC();
+}

@@ -1,0 +1,476 @@
+// Bandwidth-bound pieces of the worker gradient (Alg. 1, worker step 4): batch normalisation,
+// ReLU, residual shortcut, pooling, softmax cross-entropy.  Activations are [rows][C] with C
+// contiguous; a workgroup is laid out as (row lanes) x (C/4 sixteen-byte columns), so every
+// wavefront reads whole contiguous rows and per-channel sums are reduced across row lanes in a
+// fixed tree order (results do not depend on timing).
+#include "common.hpp"
+#include "../../include/dssp_kernels.h"
+
+namespace {
+
+constexpr int THREADS = 256;
+
+// ------------------------------------------------------------------ elementwise
+__global__ __launch_bounds__(THREADS) void relu_bwd_kernel(float* __restrict__ dy, const float* __restrict__ a, long n4, long n) {
+    float4* d4 = reinterpret_cast<float4*>(dy);
+    const float4* a4 = reinterpret_cast<const float4*>(a);
+    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < n4; i += (long)gridDim.x * THREADS) {
+        float4 d = d4[i];
+        const float4 v = a4[i];
+        d.x = v.x > 0.f ? d.x : 0.f; d.y = v.y > 0.f ? d.y : 0.f;
+        d.z = v.z > 0.f ? d.z : 0.f; d.w = v.w > 0.f ? d.w : 0.f;
+        d4[i] = d;
+    }
+    if (blockIdx.x == 0) {
+        const long t = n4 * 4 + threadIdx.x;
+        if (t < n) dy[t] = a[t] > 0.f ? dy[t] : 0.f;
+    }
+}
+
+__global__ __launch_bounds__(THREADS) void add_kernel(float* __restrict__ out, const float* __restrict__ in, long n4, long n) {
+    float4* o4 = reinterpret_cast<float4*>(out);
+    const float4* i4 = reinterpret_cast<const float4*>(in);
+    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < n4; i += (long)gridDim.x * THREADS) {
+        float4 o = o4[i];
+        const float4 v = i4[i];
+        o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+        o4[i] = o;
+    }
+    if (blockIdx.x == 0) {
+        const long t = n4 * 4 + threadIdx.x;
+        if (t < n) out[t] += in[t];
+    }
+}
+
+// ------------------------------------------------------------------ max pooling 3x3 / 2
+__global__ __launch_bounds__(THREADS) void maxpool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                              uint8_t* __restrict__ arg, int N, int H, int W, int C, int Ho, int Wo) {
+    const long total = (long)N * Ho * Wo * C;
+    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < total; i += (long)gridDim.x * THREADS) {
+        const int c = (int)(i % C);
+        long r = i / C;
+        const int wo = (int)(r % Wo); r /= Wo;
+        const int ho = (int)(r % Ho);
+        const int n = (int)(r / Ho);
+        const float* base = x + (((long)n * H + 2 * ho) * W + 2 * wo) * C + c;
+        float best = base[0];
+        int bi = 0;
+#pragma unroll
+        for (int k = 1; k < 9; ++k) {
+            const float v = base[((long)(k / 3) * W + (k % 3)) * C];
+            if (v > best) { best = v; bi = k; }
+        }
+        y[i] = best;
+        arg[i] = (uint8_t)bi;
+    }
+}
+
+// Gather form: each input element sums the windows that chose it (no atomics, fixed order).
+__global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const float* __restrict__ dy, const uint8_t* __restrict__ arg,
+                                                              float* __restrict__ dx, int N, int H, int W, int C, int Ho, int Wo) {
+    const long total = (long)N * H * W * C;
+    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < total; i += (long)gridDim.x * THREADS) {
+        const int c = (int)(i % C);
+        long r = i / C;
+        const int wi = (int)(r % W); r /= W;
+        const int hi = (int)(r % H);
+        const int n = (int)(r / H);
+        float s = 0.f;
+        const int ho_lo = hi >= 2 ? (hi - 1) / 2 : 0, ho_hi = min(Ho - 1, hi / 2);
+        const int wo_lo = wi >= 2 ? (wi - 1) / 2 : 0, wo_hi = min(Wo - 1, wi / 2);
+        for (int ho = ho_lo; ho <= ho_hi; ++ho)
+            for (int wo = wo_lo; wo <= wo_hi; ++wo) {
+                const long o = (((long)n * Ho + ho) * Wo + wo) * C + c;
+                if (arg[o] == (hi - 2 * ho) * 3 + (wi - 2 * wo)) s += dy[o];
+            }
+        dx[i] = s;
+    }
+}
+
+// ------------------------------------------------------------------ batch normalisation
+struct BnLayout {
+    int VC, RL;          // 16-byte columns per row, row lanes per workgroup
+    long rows_per_block;
+    int G;               // workgroups / partial results
+};
+
+__host__ __device__ inline BnLayout bn_layout(long M, int C) {
+    BnLayout L;
+    L.VC = C / 4;
+    L.RL = THREADS / L.VC;
+    long rpb = (M + 511) / 512;                     // at most 512 partials
+    if (rpb < 256) rpb = 256;
+    rpb = (rpb + L.RL - 1) / L.RL * L.RL;
+    L.rows_per_block = rpb;
+    L.G = (int)((M + rpb - 1) / rpb);
+    return L;
+}
+
+// Reduce one float4 per thread across the row lanes of the workgroup (tree, fixed order).
+// Result valid in row lane 0.
+__device__ __forceinline__ float4 reduce_rows(float4 v, float4* red, int rl, int vc, int RL, int VC) {
+    red[rl * VC + vc] = v;
+    __syncthreads();
+    for (int s = RL >> 1; s >= 1; s >>= 1) {
+        if (rl < s) {
+            float4 a = red[rl * VC + vc];
+            const float4 b = red[(rl + s) * VC + vc];
+            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            red[rl * VC + vc] = a;
+        }
+        __syncthreads();
+    }
+    const float4 out = red[vc];
+    __syncthreads();
+    return out;
+}
+
+// Per slab of rows: mean and sum of squared deviations per channel.  Sums are taken about a
+// pivot (the slab's first row) so that no large-minus-large cancellation occurs.
+// partial[(g*C + c)*2 + {0,1}] = {mean_g, M2_g}
+__global__ __launch_bounds__(THREADS) void bn_stats_partial_kernel(const float* __restrict__ x, float* __restrict__ partial, long M, int C) {
+    __shared__ float4 red[THREADS];
+    const BnLayout L = bn_layout(M, C);
+    const int rl = threadIdx.x / L.VC, vc = threadIdx.x % L.VC;
+    const long r0 = (long)blockIdx.x * L.rows_per_block;
+    const long r1 = min(M, r0 + L.rows_per_block);
+    const float4 pivot = *reinterpret_cast<const float4*>(x + r0 * C + 4 * vc);
+    float4 s1 = make_float4(0.f, 0.f, 0.f, 0.f), s2 = s1;
+    for (long r = r0 + rl; r < r1; r += L.RL) {
+        const float4 v = *reinterpret_cast<const float4*>(x + r * C + 4 * vc);
+        const float dx_ = v.x - pivot.x, dy_ = v.y - pivot.y, dz_ = v.z - pivot.z, dw_ = v.w - pivot.w;
+        s1.x += dx_; s1.y += dy_; s1.z += dz_; s1.w += dw_;
+        s2.x = fmaf(dx_, dx_, s2.x); s2.y = fmaf(dy_, dy_, s2.y); s2.z = fmaf(dz_, dz_, s2.z); s2.w = fmaf(dw_, dw_, s2.w);
+    }
+    s1 = reduce_rows(s1, red, rl, vc, L.RL, L.VC);
+    s2 = reduce_rows(s2, red, rl, vc, L.RL, L.VC);
+    if (rl == 0) {
+        const float n = (float)(r1 - r0);
+        float* out = partial + ((long)blockIdx.x * C + 4 * vc) * 2;
+        out[0] = pivot.x + s1.x / n; out[1] = s2.x - s1.x * s1.x / n;
+        out[2] = pivot.y + s1.y / n; out[3] = s2.y - s1.y * s1.y / n;
+        out[4] = pivot.z + s1.z / n; out[5] = s2.z - s1.z * s1.z / n;
+        out[6] = pivot.w + s1.w / n; out[7] = s2.w - s1.w * s1.w / n;
+    }
+}
+
+// Sum `v` over the SUB lanes that share a channel (tree in LDS); result broadcast to all of them.
+__device__ __forceinline__ float reduce_sub(float v, float* red, int c, int sub, int SUB, int C) {
+    red[sub * C + c] = v;
+    __syncthreads();
+    for (int s = SUB >> 1; s >= 1; s >>= 1) {
+        if (sub < s) red[sub * C + c] += red[(sub + s) * C + c];
+        __syncthreads();
+    }
+    const float out = red[c];
+    __syncthreads();
+    return out;
+}
+
+// Combine the slab results: mean = sum n_g mean_g / M, M2 = sum (M2_g + n_g (mean_g - mean)^2).
+// stats[c] = mean, stats[C + c] = 1 / sqrt(M2 / M + eps).  One workgroup, THREADS / C lanes per channel.
+__global__ __launch_bounds__(THREADS) void bn_stats_final_kernel(const float* __restrict__ partial, float* __restrict__ stats,
+                                                                 long M, int C, float eps) {
+    __shared__ float red[THREADS];
+    const BnLayout L = bn_layout(M, C);
+    const int SUB = THREADS / C;
+    const int c = threadIdx.x % C, sub = threadIdx.x / C;
+    float s = 0.f;
+    for (int g = sub; g < L.G; g += SUB) {
+        const float n = (float)(min(M, (long)(g + 1) * L.rows_per_block) - (long)g * L.rows_per_block);
+        s = fmaf(n, partial[((long)g * C + c) * 2], s);
+    }
+    const float mean = reduce_sub(s, red, c, sub, SUB, C) / (float)M;
+    float m2 = 0.f;
+    for (int g = sub; g < L.G; g += SUB) {
+        const float n = (float)(min(M, (long)(g + 1) * L.rows_per_block) - (long)g * L.rows_per_block);
+        const float d = partial[((long)g * C + c) * 2] - mean;
+        m2 += partial[((long)g * C + c) * 2 + 1] + n * d * d;
+    }
+    m2 = reduce_sub(m2, red, c, sub, SUB, C);
+    if (sub == 0) {
+        stats[c] = mean;
+        stats[C + c] = 1.0f / sqrtf(m2 / (float)M + eps);
+    }
+}
+
+// y = gamma * (x - mean) * invstd + beta (+ shortcut) (ReLU)
+template <int SC_MODE>
+__global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restrict__ x, const float* __restrict__ gamma,
+                                                           const float* __restrict__ beta, const float* __restrict__ stats,
+                                                           float* __restrict__ y, long M, int C, int relu,
+                                                           const float* __restrict__ sc, int sc_ho, int sc_wo) {
+    const int VC = C / 4;
+    const long total = M * VC;
+    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < total; i += (long)gridDim.x * THREADS) {
+        const int vc = (int)(i % VC);
+        const long row = i / VC;
+        const float4 v = *reinterpret_cast<const float4*>(x + row * C + 4 * vc);
+        const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
+        const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
+        const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
+        const float4 be = *reinterpret_cast<const float4*>(beta + 4 * vc);
+        float4 o;
+        o.x = fmaf((v.x - mu.x) * is.x, ga.x, be.x);
+        o.y = fmaf((v.y - mu.y) * is.y, ga.y, be.y);
+        o.z = fmaf((v.z - mu.z) * is.z, ga.z, be.z);
+        o.w = fmaf((v.w - mu.w) * is.w, ga.w, be.w);
+        if constexpr (SC_MODE == 1) {
+            const float4 s = *reinterpret_cast<const float4*>(sc + row * C + 4 * vc);
+            o.x += s.x; o.y += s.y; o.z += s.z; o.w += s.w;
+        } else if constexpr (SC_MODE == 2) {
+            if (4 * vc < C / 2) {        // first half of the channels: input pixel (2ho, 2wo), C/2 channels wide
+                const int wo = (int)(row % sc_wo);
+                const int ho = (int)((row / sc_wo) % sc_ho);
+                const long n = row / ((long)sc_wo * sc_ho);
+                const float4 s = *reinterpret_cast<const float4*>(
+                    sc + ((n * (2 * sc_ho) + 2 * ho) * (2 * sc_wo) + 2 * wo) * (C / 2) + 4 * vc);
+                o.x += s.x; o.y += s.y; o.z += s.z; o.w += s.w;
+            }
+        }
+        if (relu) { o.x = fmaxf(o.x, 0.f); o.y = fmaxf(o.y, 0.f); o.z = fmaxf(o.z, 0.f); o.w = fmaxf(o.w, 0.f); }
+        *reinterpret_cast<float4*>(y + row * C + 4 * vc) = o;
+    }
+}
+
+// Per slab: sum dz and sum dz * xhat per channel, dz = da * [out > 0] (written back in place).
+// partial[(g*C + c)*2 + {0,1}]
+__global__ __launch_bounds__(THREADS) void bn_bwd_partial_kernel(const float* __restrict__ x, const float* __restrict__ stats,
+                                                                 float* __restrict__ da, const float* __restrict__ out,
+                                                                 float* __restrict__ partial, long M, int C) {
+    __shared__ float4 red[THREADS];
+    const BnLayout L = bn_layout(M, C);
+    const int rl = threadIdx.x / L.VC, vc = threadIdx.x % L.VC;
+    const long r0 = (long)blockIdx.x * L.rows_per_block;
+    const long r1 = min(M, r0 + L.rows_per_block);
+    const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
+    const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
+    float4 sb = make_float4(0.f, 0.f, 0.f, 0.f), sg = sb;
+    for (long r = r0 + rl; r < r1; r += L.RL) {
+        float4 d = *reinterpret_cast<const float4*>(da + r * C + 4 * vc);
+        if (out) {
+            const float4 o = *reinterpret_cast<const float4*>(out + r * C + 4 * vc);
+            d.x = o.x > 0.f ? d.x : 0.f; d.y = o.y > 0.f ? d.y : 0.f;
+            d.z = o.z > 0.f ? d.z : 0.f; d.w = o.w > 0.f ? d.w : 0.f;
+            *reinterpret_cast<float4*>(da + r * C + 4 * vc) = d;
+        }
+        const float4 v = *reinterpret_cast<const float4*>(x + r * C + 4 * vc);
+        sb.x += d.x; sb.y += d.y; sb.z += d.z; sb.w += d.w;
+        sg.x = fmaf(d.x, (v.x - mu.x) * is.x, sg.x);
+        sg.y = fmaf(d.y, (v.y - mu.y) * is.y, sg.y);
+        sg.z = fmaf(d.z, (v.z - mu.z) * is.z, sg.z);
+        sg.w = fmaf(d.w, (v.w - mu.w) * is.w, sg.w);
+    }
+    sb = reduce_rows(sb, red, rl, vc, L.RL, L.VC);
+    sg = reduce_rows(sg, red, rl, vc, L.RL, L.VC);
+    if (rl == 0) {
+        float* o = partial + ((long)blockIdx.x * C + 4 * vc) * 2;
+        o[0] = sb.x; o[1] = sg.x; o[2] = sb.y; o[3] = sg.y; o[4] = sb.z; o[5] = sg.z; o[6] = sb.w; o[7] = sg.w;
+    }
+}
+
+__global__ __launch_bounds__(THREADS) void bn_bwd_final_kernel(const float* __restrict__ partial, float* __restrict__ dgamma,
+                                                               float* __restrict__ dbeta, long M, int C) {
+    __shared__ float red[THREADS];
+    const BnLayout L = bn_layout(M, C);
+    const int SUB = THREADS / C;
+    const int c = threadIdx.x % C, sub = threadIdx.x / C;
+    float sb = 0.f, sg = 0.f;
+    for (int g = sub; g < L.G; g += SUB) {
+        sb += partial[((long)g * C + c) * 2];
+        sg += partial[((long)g * C + c) * 2 + 1];
+    }
+    sb = reduce_sub(sb, red, c, sub, SUB, C);
+    sg = reduce_sub(sg, red, c, sub, SUB, C);
+    if (sub == 0) { dbeta[c] = sb; dgamma[c] = sg; }
+}
+
+// dx = gamma * invstd * (dz - dbeta / M - xhat * dgamma / M)
+__global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restrict__ x, const float* __restrict__ gamma,
+                                                            const float* __restrict__ stats, const float* __restrict__ dz,
+                                                            const float* __restrict__ dgamma, const float* __restrict__ dbeta,
+                                                            float* __restrict__ dx, long M, int C) {
+    const int VC = C / 4;
+    const long total = M * VC;
+    const float inv_m = 1.0f / (float)M;
+    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < total; i += (long)gridDim.x * THREADS) {
+        const int vc = (int)(i % VC);
+        const long row = i / VC;
+        const float4 v = *reinterpret_cast<const float4*>(x + row * C + 4 * vc);
+        const float4 d = *reinterpret_cast<const float4*>(dz + row * C + 4 * vc);
+        const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
+        const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
+        const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
+        const float4 dg = *reinterpret_cast<const float4*>(dgamma + 4 * vc);
+        const float4 db = *reinterpret_cast<const float4*>(dbeta + 4 * vc);
+        float4 o;
+        o.x = ga.x * is.x * (d.x - db.x * inv_m - (v.x - mu.x) * is.x * (dg.x * inv_m));
+        o.y = ga.y * is.y * (d.y - db.y * inv_m - (v.y - mu.y) * is.y * (dg.y * inv_m));
+        o.z = ga.z * is.z * (d.z - db.z * inv_m - (v.z - mu.z) * is.z * (dg.z * inv_m));
+        o.w = ga.w * is.w * (d.w - db.w * inv_m - (v.w - mu.w) * is.w * (dg.w * inv_m));
+        *reinterpret_cast<float4*>(dx + row * C + 4 * vc) = o;
+    }
+}
+
+// dx[n][2ho][2wo][c] += dy[n][ho][wo][c], c < C/2
+__global__ __launch_bounds__(THREADS) void shortcut_bwd_acc_kernel(const float* __restrict__ dy, float* __restrict__ dx,
+                                                                   int N, int Ho, int Wo, int C) {
+    const int Ch = C / 2, VC = Ch / 4;
+    const long total = (long)N * Ho * Wo * VC;
+    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < total; i += (long)gridDim.x * THREADS) {
+        const int vc = (int)(i % VC);
+        long r = i / VC;
+        const int wo = (int)(r % Wo); r /= Wo;
+        const int ho = (int)(r % Ho);
+        const long n = r / Ho;
+        const float4 d = *reinterpret_cast<const float4*>(dy + (((n * Ho + ho) * Wo + wo) * C) + 4 * vc);
+        float4* p = reinterpret_cast<float4*>(dx + ((n * (2 * Ho) + 2 * ho) * (2 * Wo) + 2 * wo) * Ch + 4 * vc);
+        float4 o = *p;
+        o.x += d.x; o.y += d.y; o.z += d.z; o.w += d.w;
+        *p = o;
+    }
+}
+
+// ------------------------------------------------------------------ global average pooling
+__global__ __launch_bounds__(THREADS) void gap_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int N, int HW, int C) {
+    const int i = blockIdx.x * THREADS + threadIdx.x;
+    if (i >= N * C) return;
+    const int n = i / C, c = i % C;
+    float s = 0.f;
+    for (int k = 0; k < HW; ++k) s += x[((long)n * HW + k) * C + c];
+    y[i] = s / (float)HW;
+}
+
+__global__ __launch_bounds__(THREADS) void gap_bwd_kernel(const float* __restrict__ dy, float* __restrict__ dx, int N, int HW, int C) {
+    const long total = (long)N * HW * C;
+    const float inv = 1.0f / (float)HW;
+    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < total; i += (long)gridDim.x * THREADS) {
+        const int c = (int)(i % C);
+        const long n = i / ((long)HW * C);
+        dx[i] = dy[n * C + c] * inv;
+    }
+}
+
+// ------------------------------------------------------------------ softmax cross-entropy
+// One thread per sample; the batch mean of the loss is summed by thread 0 in index order.
+__global__ void softmax_xent_kernel(const float* __restrict__ z, const int32_t* __restrict__ label,
+                                    float* __restrict__ dz, float* __restrict__ loss, int m, int C) {
+    extern __shared__ float row_loss[];
+    const int i = threadIdx.x;
+    if (i < m) {
+        const float* zi = z + (long)i * C;
+        float mx = zi[0];
+        for (int j = 1; j < C; ++j) mx = fmaxf(mx, zi[j]);
+        float se = 0.f;
+        for (int j = 0; j < C; ++j) se += expf(zi[j] - mx);
+        const int y = label[i];
+        row_loss[i] = logf(se) + mx - zi[y];
+        const float inv = 1.0f / se, invm = 1.0f / (float)m;
+        for (int j = 0; j < C; ++j) dz[(long)i * C + j] = (expf(zi[j] - mx) * inv - (j == y ? 1.f : 0.f)) * invm;
+    }
+    __syncthreads();
+    if (i == 0 && loss) {
+        float s = 0.f;
+        for (int k = 0; k < m; ++k) s += row_loss[k];
+        *loss = s / (float)m;
+    }
+}
+
+inline int grid_for(long items) { return stream_grid(ceil_div(items, THREADS)); }
+inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline bool bn_ok(long M, int C) { return M >= 1 && C >= 4 && C % 4 == 0 && C <= THREADS && THREADS % C == 0; }
+
+}  // namespace
+
+extern "C" int dsspk_relu_bwd(void* stream, float* dy, const float* a, long n) {
+    if (!dy || !a || n < 0 || !al16(dy) || !al16(a)) return -1;
+    hipLaunchKernelGGL(relu_bwd_kernel, dim3(grid_for(n / 4)), dim3(THREADS), 0, (hipStream_t)stream, dy, a, n / 4, n);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_add(void* stream, float* out, const float* in, long n) {
+    if (!out || !in || n < 0 || !al16(out) || !al16(in)) return -1;
+    hipLaunchKernelGGL(add_kernel, dim3(grid_for(n / 4)), dim3(THREADS), 0, (hipStream_t)stream, out, in, n / 4, n);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_maxpool_fwd(void* stream, const float* x, float* y, uint8_t* arg, int N, int H, int W, int C) {
+    if (!x || !y || !arg || N < 1 || H < 3 || W < 3 || C < 1) return -1;
+    const int Ho = (H - 3) / 2 + 1, Wo = (W - 3) / 2 + 1;
+    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for((long)N * Ho * Wo * C)), dim3(THREADS), 0, (hipStream_t)stream,
+                       x, y, arg, N, H, W, C, Ho, Wo);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_maxpool_bwd(void* stream, const float* dy, const uint8_t* arg, float* dx, int N, int H, int W, int C) {
+    if (!dy || !dx || !arg || N < 1 || H < 3 || W < 3 || C < 1) return -1;
+    const int Ho = (H - 3) / 2 + 1, Wo = (W - 3) / 2 + 1;
+    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for((long)N * H * W * C)), dim3(THREADS), 0, (hipStream_t)stream,
+                       dy, arg, dx, N, H, W, C, Ho, Wo);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" size_t dsspk_bn_scratch_floats(long M, int C) {
+    if (!bn_ok(M, C)) return 0;
+    return (size_t)bn_layout(M, C).G * C * 2;
+}
+
+extern "C" int dsspk_bn_fwd(void* stream, const float* x, const float* gamma, const float* beta, float* y,
+                            float* stats, float* scratch, long M, int C, float eps, int relu,
+                            int shortcut_mode, const float* sc, int sc_n, int sc_ho, int sc_wo) {
+    if (!x || !gamma || !beta || !y || !stats || !scratch || !bn_ok(M, C)) return -1;
+    if (!al16(x) || !al16(y) || !al16(gamma) || !al16(beta) || !al16(stats)) return -1;
+    if (shortcut_mode < 0 || shortcut_mode > 2 || (shortcut_mode && (!sc || !al16(sc)))) return -1;
+    if (shortcut_mode == 2 && ((long)sc_n * sc_ho * sc_wo != M || C % 8)) return -1;
+    hipStream_t s = (hipStream_t)stream;
+    const BnLayout L = bn_layout(M, C);
+    hipLaunchKernelGGL(bn_stats_partial_kernel, dim3(L.G), dim3(THREADS), 0, s, x, scratch, M, C);
+    hipLaunchKernelGGL(bn_stats_final_kernel, dim3(1), dim3(THREADS), 0, s, scratch, stats, M, C, eps);
+    const int grid = grid_for(M * (C / 4));
+    if (shortcut_mode == 0)
+        hipLaunchKernelGGL((bn_apply_kernel<0>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, stats, y, M, C, relu, sc, sc_ho, sc_wo);
+    else if (shortcut_mode == 1)
+        hipLaunchKernelGGL((bn_apply_kernel<1>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, stats, y, M, C, relu, sc, sc_ho, sc_wo);
+    else
+        hipLaunchKernelGGL((bn_apply_kernel<2>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, stats, y, M, C, relu, sc, sc_ho, sc_wo);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_bn_bwd(void* stream, const float* x, const float* gamma, const float* stats, float* da,
+                            const float* out, float* dx, float* dgamma, float* dbeta, float* scratch, long M, int C) {
+    if (!x || !gamma || !stats || !da || !dx || !dgamma || !dbeta || !scratch || !bn_ok(M, C)) return -1;
+    if (!al16(x) || !al16(da) || !al16(dx) || !al16(gamma) || !al16(stats) || !al16(dgamma) || !al16(dbeta)) return -1;
+    if (out && !al16(out)) return -1;
+    hipStream_t s = (hipStream_t)stream;
+    const BnLayout L = bn_layout(M, C);
+    hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3(L.G), dim3(THREADS), 0, s, x, stats, da, out, scratch, M, C);
+    hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(1), dim3(THREADS), 0, s, scratch, dgamma, dbeta, M, C);
+    hipLaunchKernelGGL(bn_bwd_dx_kernel, dim3(grid_for(M * (C / 4))), dim3(THREADS), 0, s, x, gamma, stats, da, dgamma, dbeta, dx, M, C);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_shortcut_bwd_acc(void* stream, const float* dy, float* dx, int N, int Ho, int Wo, int C) {
+    if (!dy || !dx || N < 1 || Ho < 1 || Wo < 1 || C < 8 || C % 8 || !al16(dy) || !al16(dx)) return -1;
+    hipLaunchKernelGGL(shortcut_bwd_acc_kernel, dim3(grid_for((long)N * Ho * Wo * (C / 8))), dim3(THREADS), 0,
+                       (hipStream_t)stream, dy, dx, N, Ho, Wo, C);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_gap_fwd(void* stream, const float* x, float* y, int N, int HW, int C) {
+    if (!x || !y || N < 1 || HW < 1 || C < 1) return -1;
+    hipLaunchKernelGGL(gap_fwd_kernel, dim3(ceil_div((long)N * C, THREADS)), dim3(THREADS), 0, (hipStream_t)stream, x, y, N, HW, C);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_gap_bwd(void* stream, const float* dy, float* dx, int N, int HW, int C) {
+    if (!dy || !dx || N < 1 || HW < 1 || C < 1) return -1;
+    hipLaunchKernelGGL(gap_bwd_kernel, dim3(grid_for((long)N * HW * C)), dim3(THREADS), 0, (hipStream_t)stream, dy, dx, N, HW, C);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_softmax_xent(void* stream, const float* z, const int32_t* y, float* dz, float* loss, int m, int C) {
+    if (!z || !y || !dz || m < 1 || m > 1024 || C < 1 || C > 1024) return -1;
+    const int threads = (m + 63) / 64 * 64;
+    hipLaunchKernelGGL(softmax_xent_kernel, dim3(1), dim3(threads), sizeof(float) * m, (hipStream_t)stream, z, y, dz, loss, m, C);
+    return DSSPK_LAUNCH_RC();
+}

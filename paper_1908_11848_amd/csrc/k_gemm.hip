@@ -1,0 +1,109 @@
+// Fully connected layers: C = op(A) * op(B) (+ bias) (ReLU), fp32 on the matrix cores.
+// One workgroup (4 wavefronts) owns a 64 x 64 tile of C; wavefront w owns the 32 x 32
+// quadrant (w / 2, w % 2).  Operands come in through generic strides, so the same kernel
+// serves y = x W (+b), dx = dy W^T and dW = x^T dy of Alg. 1's worker gradient.
+#include "mma.hpp"
+#include "../../include/dssp_kernels.h"
+
+namespace {
+
+constexpr int BM = 64, BN = 64, THREADS = 256;
+
+// A_FAST_K: op(A) is k-contiguous in memory (a_cs == 1); otherwise row-contiguous (a_rs == 1).
+// B_FAST_N: op(B) is column-contiguous (b_cs == 1); otherwise k-contiguous (b_rs == 1).
+// The flags only select which index runs across neighbouring lanes so that loads coalesce.
+template <bool A_FAST_K, bool B_FAST_N>
+__global__ __launch_bounds__(THREADS) void gemm_kernel(const float* __restrict__ A, long a_rs, long a_cs,
+                                                       const float* __restrict__ B, long b_rs, long b_cs,
+                                                       float* __restrict__ C, long ldc, int M, int N, int K,
+                                                       const float* __restrict__ bias, int relu) {
+    __shared__ __attribute__((aligned(16))) float As[2][BM * mma::LDK];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BN * mma::LDK];      // stored [col][k]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    floatx4 acc[2][2];
+    mma::zero(acc);
+    float ra[4], rb[4];
+    auto load = [&](int k0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = tid + e * THREADS;                     // 0 .. 1023
+            const int i = A_FAST_K ? idx / 16 : idx % 64, k = A_FAST_K ? idx % 16 : idx / 64;
+            ra[e] = (m0 + i < M && k0 + k < K) ? A[(long)(m0 + i) * a_rs + (long)(k0 + k) * a_cs] : 0.f;
+            const int j = B_FAST_N ? idx % 64 : idx / 16, kb = B_FAST_N ? idx / 64 : idx % 16;
+            rb[e] = (n0 + j < N && k0 + kb < K) ? B[(long)(k0 + kb) * b_rs + (long)(n0 + j) * b_cs] : 0.f;
+        }
+    };
+    auto store = [&](int buf) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = tid + e * THREADS;
+            const int i = A_FAST_K ? idx / 16 : idx % 64, k = A_FAST_K ? idx % 16 : idx / 64;
+            As[buf][i * mma::LDK + k] = ra[e];
+            const int j = B_FAST_N ? idx % 64 : idx / 16, kb = B_FAST_N ? idx / 64 : idx % 16;
+            Bs[buf][j * mma::LDK + kb] = rb[e];
+        }
+    };
+    const int nk = (K + mma::KC - 1) / mma::KC;
+    load(0);
+    for (int kc = 0; kc < nk; ++kc) {
+        const int buf = kc & 1;
+        store(buf);
+        __syncthreads();
+        if (kc + 1 < nk) load((kc + 1) * mma::KC);
+        mma::chunk16<2, 2, false, true>(As[buf], mma::LDK, Bs[buf], mma::LDK, 32 * (wave >> 1), 32 * (wave & 1), acc, lane);
+    }
+    const int l16 = lane & 15, q = lane >> 4;
+#pragma unroll
+    for (int wm = 0; wm < 2; ++wm)
+#pragma unroll
+        for (int wn = 0; wn < 2; ++wn) {
+            const int col = n0 + 32 * (wave & 1) + 16 * wn + l16;
+            if (col >= N) continue;
+            const float bv = bias ? bias[col] : 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = m0 + 32 * (wave >> 1) + 16 * wm + 4 * q + v;
+                if (row >= M) continue;
+                float x = acc[wm][wn][v] + bv;
+                if (relu) x = fmaxf(x, 0.f);
+                C[(long)row * ldc + col] = x;
+            }
+        }
+}
+
+// out[j] = sum_i X[i][j]: one workgroup per 64 columns, 4 row groups, fixed order.
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ X, float* __restrict__ out, long M, int N) {
+    __shared__ float part[4][64];
+    const int c = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + c;
+    float s = 0.f;
+    if (col < N)
+        for (long i = g; i < M; i += 4) s += X[i * N + col];
+    part[g][c] = s;
+    __syncthreads();
+    if (g == 0 && col < N) out[col] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
+}
+
+}  // namespace
+
+extern "C" int dsspk_gemm(void* stream, const float* A, long a_rs, long a_cs, const float* B, long b_rs, long b_cs,
+                          float* C, long ldc, int M, int N, int K, const float* bias, int relu) {
+    if (!A || !B || !C || M < 1 || N < 1 || K < 1) return -1;
+    dim3 grid(ceil_div(N, BN), ceil_div(M, BM));
+    hipStream_t s = (hipStream_t)stream;
+    const bool ak = a_cs == 1, bn = b_cs == 1;
+#define GO(AK, BNF) hipLaunchKernelGGL((gemm_kernel<AK, BNF>), grid, dim3(THREADS), 0, s, A, a_rs, a_cs, B, b_rs, b_cs, C, ldc, M, N, K, bias, relu)
+    if (ak && bn) GO(true, true);
+    else if (ak) GO(true, false);
+    else if (bn) GO(false, true);
+    else GO(false, false);
+#undef GO
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_colsum(void* stream, const float* X, float* out, long M, int N) {
+    if (!X || !out || M < 1 || N < 1) return -1;
+    hipLaunchKernelGGL(colsum_kernel, dim3(ceil_div(N, 64)), dim3(256), 0, (hipStream_t)stream, X, out, M, N);
+    return DSSPK_LAUNCH_RC();
+}

@@ -1,0 +1,229 @@
+"""Each HIP kernel family against the oracle's layer function on the same seeded inputs.
+
+Sizes span several tiles and ragged tails; one case per convolution kind has the full
+benchmark shape (batch 128).  Tolerances: the kernels accumulate in fp32 (matrix cores or
+fixed-order trees), the oracle in fp64; for a sum of n products of O(1) terms the fp32 error is
+about sqrt(n) * 6e-8 relative to the operand scale, so 2e-6 relative L2 covers every case here
+with an order of magnitude to spare.  Integer outputs (arg-max positions) and copies are
+bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_1908_11848_amd import binding as B          # noqa: E402
+from gpu_util import dev, empty, host, rel_l2, stream_ptr  # noqa: E402
+
+TOL = 2e-6
+
+
+def rc(x):
+    assert x == 0, "launcher returned %d" % x
+
+
+def f32(rng, shape, scale=1.0):
+    return (rng.standard_normal(shape) * scale).astype(np.float32)
+
+
+# ------------------------------------------------------------------ server kernels
+@pytest.mark.parametrize("n", [1, 3, 4, 1023, 1 << 20, (1 << 22) + 5])
+def test_apply_and_pull(n):
+    g = np.random.default_rng(n)
+    w0, gr = f32(g, n), f32(g, n, 1e-3)
+    w, grd = dev(w0), dev(gr)
+    stamps = torch.zeros(2, dtype=torch.int64, device="cuda")
+    scale = np.float32(0.05) / np.float32(8)
+    rc(B.lib().dsspk_apply(stream_ptr(), w.data_ptr(), grd.data_ptr(), n, float(scale), stamps.data_ptr(), 7))
+    want = w0.astype(np.float64) - np.float64(scale) * gr.astype(np.float64)       # Alg. 1 server step 2
+    got = host(w)
+    assert np.all(np.abs(got - want) <= np.spacing(np.abs(want).astype(np.float32)))   # one rounding
+    dst = empty(n)
+    rc(B.lib().dsspk_pull(stream_ptr(), dst.data_ptr(), w.data_ptr(), n, stamps[1:].data_ptr(), stamps.data_ptr()))
+    assert np.array_equal(host(dst), got)                                           # bit-exact copy
+    assert host(stamps).tolist() == [7, 7]
+
+
+# ------------------------------------------------------------------ GEMM (fully connected layers)
+@pytest.mark.parametrize("m,n_in,n_out", [(32, 3072, 256), (32, 256, 10), (128, 3136, 384), (128, 192, 10),
+                                          (128, 64, 100), (37, 100, 75), (1, 16, 1)])
+def test_fc_forward_backward(oracle_nn, m, n_in, n_out):
+    g = np.random.default_rng(m * 131 + n_out)
+    x, w, b, dy = f32(g, (m, n_in)), f32(g, (n_in, n_out), 0.1), f32(g, n_out), f32(g, (m, n_out))
+    X, W, Bv, DY = dev(x), dev(w), dev(b), dev(dy)
+    y = empty((m, n_out)); dx = empty((m, n_in)); dw = empty((n_in, n_out)); db = empty(n_out)
+    s = stream_ptr()
+    L = B.lib()
+    rc(L.dsspk_gemm(s, X.data_ptr(), n_in, 1, W.data_ptr(), n_out, 1, y.data_ptr(), n_out, m, n_out, n_in, Bv.data_ptr(), 0))
+    rc(L.dsspk_gemm(s, DY.data_ptr(), n_out, 1, W.data_ptr(), 1, n_out, dx.data_ptr(), n_in, m, n_in, n_out, None, 0))
+    rc(L.dsspk_gemm(s, X.data_ptr(), 1, n_in, DY.data_ptr(), n_out, 1, dw.data_ptr(), n_out, n_in, n_out, m, None, 0))
+    rc(L.dsspk_colsum(s, DY.data_ptr(), db.data_ptr(), m, n_out))
+    x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+    yo = oracle_nn.fc_fwd(x64, w64, b.astype(np.float64))
+    dxo, dwo, dbo = oracle_nn.fc_bwd(x64, w64, dy64)
+    assert rel_l2(host(y), yo) < TOL
+    assert rel_l2(host(dx), dxo) < TOL
+    assert rel_l2(host(dw), dwo) < TOL
+    assert rel_l2(host(db), dbo) < TOL
+    yr = empty((m, n_out))
+    rc(L.dsspk_gemm(s, X.data_ptr(), n_in, 1, W.data_ptr(), n_out, 1, yr.data_ptr(), n_out, m, n_out, n_in, Bv.data_ptr(), 1))
+    assert rel_l2(host(yr), np.maximum(yo, 0)) < TOL
+
+
+# ------------------------------------------------------------------ convolution
+CONV_CASES = [  # N, H, Cin, Cout, k, stride, pad, bias+relu
+    (3, 32, 3, 16, 3, 1, 1, False),
+    (2, 32, 16, 16, 3, 1, 1, False),
+    (2, 32, 16, 32, 3, 2, 1, False),
+    (3, 16, 32, 32, 3, 1, 1, False),
+    (2, 16, 32, 64, 3, 2, 1, False),
+    (5, 8, 64, 64, 3, 1, 1, False),
+    (2, 32, 3, 64, 5, 1, 2, True),
+    (3, 15, 64, 64, 5, 1, 2, True),
+    (1, 7, 16, 16, 3, 1, 1, False),          # fewer pixels than one tile
+    (128, 32, 16, 16, 3, 1, 1, False),       # benchmark shapes, batch 128
+    (128, 16, 32, 32, 3, 1, 1, False),
+    (128, 8, 64, 64, 3, 1, 1, False),
+    (128, 32, 16, 32, 3, 2, 1, False),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv_forward_dgrad_wgrad(oracle_nn, case):
+    N, H, Cin, Cout, k, s, p, br = case
+    g = np.random.default_rng(hash(case) % (1 << 31))
+    x, w = f32(g, (N, H, H, Cin)), f32(g, (k, k, Cin, Cout), (2.0 / (k * k * Cin)) ** 0.5)
+    b = f32(g, Cout) if br else None
+    Ho = (H + 2 * p - k) // s + 1
+    dy = f32(g, (N, Ho, Ho, Cout))
+    X, W, DY = dev(x), dev(w), dev(dy)
+    Bv = dev(b) if br else None
+    st = stream_ptr()
+    L = B.lib()
+    y = empty((N, Ho, Ho, Cout))
+    rc(L.dsspk_conv_fwd(st, X.data_ptr(), W.data_ptr(), Bv.data_ptr() if br else None, y.data_ptr(),
+                        N, H, H, Cin, Cout, k, k, s, p, int(br)))
+    x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+    yo = oracle_nn.conv2d_fwd(x64, w64, b.astype(np.float64) if br else None, s, p)
+    if br:
+        yo = np.maximum(yo, 0)
+    assert rel_l2(host(y), yo) < TOL
+    assert np.max(np.abs(host(y) - yo)) < 2e-5
+    dxo, dwo, _ = oracle_nn.conv2d_bwd(x64, w64, dy64, s, p, False, need_dx=Cin % 16 == 0)
+    scratch = empty(L.dsspk_conv_wgrad_scratch_floats(N, H, H, Cin, Cout, k, k, s, p))
+    dw = empty((k, k, Cin, Cout))
+    rc(L.dsspk_conv_bwd_weight(st, X.data_ptr(), DY.data_ptr(), dw.data_ptr(), scratch.data_ptr(),
+                               N, H, H, Cin, Cout, k, k, s, p))
+    assert rel_l2(host(dw), dwo) < TOL
+    if Cin % 16 == 0:
+        dx = empty((N, H, H, Cin))
+        rc(L.dsspk_conv_bwd_data(st, DY.data_ptr(), W.data_ptr(), dx.data_ptr(), N, H, H, Cin, Cout, k, k, s, p))
+        assert rel_l2(host(dx), dxo) < TOL
+
+
+# ------------------------------------------------------------------ elementwise / pooling
+@pytest.mark.parametrize("n", [5, 64, 100003])
+def test_relu_bwd_and_add(n):
+    g = np.random.default_rng(n)
+    n4 = (n + 3) // 4 * 4
+    a, dy = f32(g, n4), f32(g, n4)
+    a[::7] = 0.0
+    A, DY = dev(a), dev(dy)
+    rc(B.lib().dsspk_relu_bwd(stream_ptr(), DY.data_ptr(), A.data_ptr(), n))
+    got = host(DY)
+    assert np.array_equal(got[:n], np.where(a[:n] > 0, dy[:n], 0)) and np.array_equal(got[n:], dy[n:])
+    rc(B.lib().dsspk_add(stream_ptr(), DY.data_ptr(), A.data_ptr(), n))
+    assert np.array_equal(host(DY)[:n], got[:n] + a[:n])
+
+
+@pytest.mark.parametrize("N,H,C", [(2, 32, 64), (3, 15, 64), (1, 5, 4), (128, 15, 64)])
+def test_maxpool(oracle_nn, N, H, C):
+    g = np.random.default_rng(H)
+    x = f32(g, (N, H, H, C))
+    Ho = (H - 3) // 2 + 1
+    dy = f32(g, (N, Ho, Ho, C))
+    X, DY = dev(x), dev(dy)
+    y = empty((N, Ho, Ho, C)); arg = empty((N, Ho, Ho, C), torch.uint8); dx = empty((N, H, H, C))
+    rc(B.lib().dsspk_maxpool_fwd(stream_ptr(), X.data_ptr(), y.data_ptr(), arg.data_ptr(), N, H, H, C))
+    rc(B.lib().dsspk_maxpool_bwd(stream_ptr(), DY.data_ptr(), arg.data_ptr(), dx.data_ptr(), N, H, H, C))
+    yo, argo, _ = oracle_nn.maxpool_fwd(x.astype(np.float64), 3, 2, None, 0.0)
+    assert np.array_equal(host(arg), argo.astype(np.uint8))           # same inputs, exact comparisons
+    assert np.array_equal(host(y).astype(np.float64), yo)
+    dxo = oracle_nn.maxpool_bwd(dy.astype(np.float64), argo, x.shape, 3, 2)
+    assert rel_l2(host(dx), dxo) < TOL
+
+
+# ------------------------------------------------------------------ batch normalisation (+ shortcut, ReLU)
+@pytest.mark.parametrize("N,H,C,mode,relu", [(5, 32, 16, 0, 1), (3, 16, 32, 1, 1), (5, 8, 64, 2, 1), (2, 16, 32, 2, 1),
+                                             (3, 7, 16, 0, 0), (128, 32, 16, 1, 1), (128, 8, 64, 0, 1)])
+def test_batchnorm_forward_backward(oracle_nn, N, H, C, mode, relu):
+    g = np.random.default_rng(N * 1000 + H * 10 + mode)
+    M = N * H * H
+    x = f32(g, (N, H, H, C), 2.0) + np.float32(1.5)
+    gamma, beta = (1 + 0.2 * g.standard_normal(C)).astype(np.float32), f32(g, C, 0.3)
+    da = f32(g, (N, H, H, C))
+    sc = None
+    if mode == 1:
+        sc = f32(g, (N, H, H, C))
+    elif mode == 2:
+        sc = f32(g, (N, 2 * H, 2 * H, C // 2))
+    L = B.lib()
+    st = stream_ptr()
+    X, Ga, Be, DA = dev(x), dev(gamma), dev(beta), dev(da)
+    SC = dev(sc) if sc is not None else None
+    y = empty((N, H, H, C)); stats = empty(2 * C); scratch = empty(L.dsspk_bn_scratch_floats(M, C))
+    rc(L.dsspk_bn_fwd(st, X.data_ptr(), Ga.data_ptr(), Be.data_ptr(), y.data_ptr(), stats.data_ptr(), scratch.data_ptr(),
+                      M, C, 1e-5, relu, mode, SC.data_ptr() if SC is not None else None, N, H, H))
+    x64 = x.astype(np.float64)
+    yo, mean, invstd = oracle_nn.bn_fwd(x64, gamma.astype(np.float64), beta.astype(np.float64))
+    if mode == 1:
+        yo = yo + sc
+    elif mode == 2:
+        yo = yo + oracle_nn.shortcut_pad_fwd(sc.astype(np.float64), C)
+    zo = yo
+    if relu:
+        yo = np.maximum(yo, 0)
+    assert rel_l2(host(stats)[:C], mean) < TOL and rel_l2(host(stats)[C:], invstd) < TOL
+    got = host(y)
+    assert rel_l2(got, yo) < TOL
+    # backward; the ReLU mask is taken from the saved forward output on both sides
+    dx = empty((N, H, H, C)); dgam = empty(C); dbet = empty(C)
+    rc(L.dsspk_bn_bwd(st, X.data_ptr(), Ga.data_ptr(), stats.data_ptr(), DA.data_ptr(), y.data_ptr() if relu else None,
+                      dx.data_ptr(), dgam.data_ptr(), dbet.data_ptr(), scratch.data_ptr(), M, C))
+    mask = (got > 0) if relu else np.ones_like(got, dtype=bool)
+    near = np.abs(zo) < 1e-5                                  # decisions the two precisions may take differently
+    assert np.array_equal(mask[~near], (zo > 0)[~near] if relu else mask[~near])
+    dz = np.where(mask, da, 0).astype(np.float64)
+    dxo, dgo, dbo = oracle_nn.bn_bwd(x64, gamma.astype(np.float64), mean, invstd, dz)
+    assert np.array_equal(host(DA), dz.astype(np.float32))    # masked gradient written back in place
+    assert rel_l2(host(dx), dxo) < 5e-6
+    assert rel_l2(host(dgam), dgo) < TOL and rel_l2(host(dbet), dbo) < TOL
+
+
+def test_shortcut_gap_softmax(oracle_nn):
+    g = np.random.default_rng(5)
+    L = B.lib()
+    st = stream_ptr()
+    N, Ho, C = 3, 8, 64
+    dy, dx0 = f32(g, (N, Ho, Ho, C)), f32(g, (N, 2 * Ho, 2 * Ho, C // 2))
+    DY, DX = dev(dy), dev(dx0)
+    rc(L.dsspk_shortcut_bwd_acc(st, DY.data_ptr(), DX.data_ptr(), N, Ho, Ho, C))
+    want = dx0.astype(np.float64)
+    oracle_nn.shortcut_pad_bwd_acc(dy.astype(np.float64), want)
+    assert rel_l2(host(DX), want) < 1e-7
+    x = f32(g, (5, 8, 8, 64))
+    X = dev(x); y = empty((5, 64)); dxx = empty((5, 8, 8, 64))
+    rc(L.dsspk_gap_fwd(st, X.data_ptr(), y.data_ptr(), 5, 64, 64))
+    assert rel_l2(host(y), oracle_nn.gap_fwd(x.astype(np.float64))) < TOL
+    rc(L.dsspk_gap_bwd(st, y.data_ptr(), dxx.data_ptr(), 5, 64, 64))
+    assert rel_l2(host(dxx), oracle_nn.gap_bwd(host(y).astype(np.float64), x.shape)) < TOL
+    for m, C in [(128, 100), (32, 10), (7, 3)]:
+        z = f32(g, (m, C), 4.0)
+        lab = g.integers(0, C, m).astype(np.int32)
+        Z, Y = dev(z), dev(lab)
+        dz = empty((m, C)); loss = empty(1)
+        rc(L.dsspk_softmax_xent(st, Z.data_ptr(), Y.data_ptr(), dz.data_ptr(), loss.data_ptr(), m, C))
+        lo, dzo = oracle_nn.softmax_xent(z.astype(np.float64), lab)
+        assert abs(host(loss)[0] - lo) < 2e-6 * max(1, abs(lo))
+        assert rel_l2(host(dz), dzo) < TOL
