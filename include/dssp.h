@@ -11,6 +11,8 @@
  * General rules
  *  - All pointers named *_dev are DEVICE pointers owned by the caller and only
  *    borrowed for the duration documented per call; all others are HOST pointers.
+ *    Parameter, gradient, snapshot and image buffers must be 16-byte aligned (the
+ *    kernels move 16-byte vectors); a misaligned buffer is rejected with DSSP_EHIP.
  *  - Every call returns DSSP_OK (0) or a negative error code; nothing throws.
  *    dssp_last_error() gives a readable message for the last failing call on that
  *    context (valid until the next call on it).

@@ -18,10 +18,12 @@ import numpy as np
 from . import dssp_rules
 
 
-def run(K, s_L, r_max, lr, w0, durations, grad_fn, quota=None, total=None, keep_grads=False):
+def run(K, s_L, r_max, lr, w0, durations, grad_fn, quota=None, total=None, keep_grads=False,
+        keep_snapshots=False):
     """grad_fn(p, n, w_local) -> (loss, g): gradient of worker p's n-th iteration
     (n from 0) on its local weights.  Returns dict(log, w, state, stats, pushes)
-    where pushes[i] = dict(worker, n, pulled_version, loss[, g]) in apply order."""
+    where pushes[i] = dict(worker, n, pulled_version, loss[, g][, w_local]) in apply order
+    (w_local: the snapshot the gradient was computed on, narrowed to float32)."""
     w = np.array(w0, dtype=np.float64)
     scale = float(lr) / float(K)
     w_local = [None] * K
@@ -35,6 +37,8 @@ def run(K, s_L, r_max, lr, w0, durations, grad_fn, quota=None, total=None, keep_
         rec = dict(worker=p, n=n, pulled_version=pulled_version, loss=loss)
         if keep_grads:
             rec["g"] = np.array(g, dtype=np.float64)
+        if keep_snapshots:
+            rec["w_local"] = w_local[p].astype(np.float32)
         pushes.append(rec)
         np.subtract(w, scale * np.asarray(g, dtype=np.float64), out=w)
 

@@ -1,0 +1,105 @@
+"""One emulated DSSP cluster on one GPU: device buffers and streams (through torch, which is
+used for nothing else), the library context, and the virtual-time schedule.
+
+Every arithmetic step runs inside libdssp (pull, worker gradient, apply, decisions); this class
+only owns memory and calls the C ABI through `binding`.
+"""
+import numpy as np
+import torch
+
+from . import binding as B
+from . import driver
+
+
+class Emulation:
+    def __init__(self, model, K, s_L, r_max, lr, w0, batch=0, n_classes=0, xs=None, ys=None, grads=None,
+                 device="cuda:0"):
+        """model: 'mlp' | 'alexnet_ds' | 'resnet<d>' | 'none'.
+        w0: float32 initial weights.  xs[p][j] / ys[p][j]: pool of mini-batches of worker p
+        (cycled); grads[p]: fixed gradient buffers for model 'none' (server stress)."""
+        if not torch.cuda.is_available():
+            raise RuntimeError("a GPU is required")
+        B.lib()
+        self.dev = torch.device(device)
+        torch.cuda.set_device(self.dev)
+        self.model, self.mid = model, B.model_id(model)
+        self.K, self.batch, self.n_classes = K, batch, n_classes
+        n = int(np.asarray(w0).size)
+        self.n = n
+        self.w = torch.from_numpy(np.ascontiguousarray(w0, dtype=np.float32)).to(self.dev)
+        # one row per worker; rows start 256-byte aligned (the library moves 16-byte vectors)
+        pitch = (n + 63) // 64 * 64
+        self.w_local = torch.empty((K, pitch), dtype=torch.float32, device=self.dev)[:, :n]
+        self.grad = torch.zeros((K, pitch), dtype=torch.float32, device=self.dev)[:, :n]
+        if grads is not None:
+            for p in range(K):
+                self.grad[p].copy_(torch.from_numpy(np.ascontiguousarray(grads[p], dtype=np.float32)))
+        self.loss = torch.zeros(K, dtype=torch.float32, device=self.dev)
+        self.streams = [torch.cuda.Stream(device=self.dev) for _ in range(K + 1)]
+        self.ctx = B.dssp_create(self.w, n, K, s_L, r_max, lr)
+        B.dssp_set_stream(self.ctx, -1, self.streams[K])
+        for p in range(K):
+            B.dssp_set_stream(self.ctx, p, self.streams[p])
+        self.ws = None
+        if self.mid != B.DSSP_MODEL_NONE:
+            nbytes = B.dssp_workspace_bytes(self.mid, batch, n_classes, K)
+            self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+            B.dssp_set_model(self.ctx, self.mid, batch, n_classes, self.ws, nbytes)
+            self.xs = [[torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.dev) for x in row] for row in xs]
+            self.ys = [[torch.from_numpy(np.ascontiguousarray(y, dtype=np.int32)).to(self.dev) for y in row] for row in ys]
+        torch.cuda.synchronize()
+        self.on_step = None            # test hook: called after a worker step was enqueued
+        self.before_step = None        # test hook: called after the pull, before the step is enqueued
+
+    # ------------------------------------------------------------------ pieces
+    def step(self, p, n):
+        """Enqueue worker p's n-th iteration (n from 0) on its stream."""
+        if self.mid == B.DSSP_MODEL_NONE:
+            return
+        j = n % len(self.xs[p])
+        if self.before_step:
+            self.before_step(p, n)
+        B.dssp_worker_step(self.ctx, p, self.xs[p][j], self.ys[p][j], self.w_local[p], self.grad[p],
+                           self.loss[p:p + 1])
+        if self.on_step:
+            self.on_step(p, n)
+
+    def run(self, durations, quota=None, total=None, log=True):
+        out = driver.run_schedule(self.ctx, self.K, durations, quota=quota, total=total,
+                                  grad_ptr=lambda p: self.grad[p], pull_dst=lambda p: self.w_local[p],
+                                  step=self.step, log=log)
+        return out
+
+    def synchronize(self):
+        B.dssp_synchronize(self.ctx)
+
+    def weights(self):
+        self.synchronize()
+        return self.w.cpu().numpy()
+
+    def worker_grad(self, p):
+        torch.cuda.current_stream().synchronize()
+        self.streams[p].synchronize()
+        return self.grad[p].cpu().numpy(), float(self.loss[p].item())
+
+    def workspace_tensor(self, p, what, index):
+        """Saved tensor of worker p's last step (see dssp_workspace_tensor) as numpy, or None."""
+        loc = B.dssp_workspace_tensor(self.mid, self.batch, self.n_classes, self.K, p, what, index)
+        if loc is None:
+            return None
+        off, cnt = loc
+        self.streams[p].synchronize()
+        if what == 1:
+            return self.ws[off:off + cnt].cpu().numpy()
+        return self.ws[off:off + 4 * cnt].view(torch.float32).cpu().numpy()
+
+    def close(self):
+        if self.ctx is not None:
+            B.dssp_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
