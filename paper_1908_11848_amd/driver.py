@@ -17,57 +17,76 @@ from . import binding as B
 PUSH, CTRL, OK, BLOCK, RELEASE, PULL = 0, 1, 2, 3, 4, 5
 
 
+class Schedule:
+    """Resumable schedule: advance(n) processes the next n pushes."""
+
+    def __init__(self, ctx, K, durations, quota=None, grad_ptr=None, pull_dst=None, step=None, log=True):
+        """grad_ptr(p) -> device pointer of worker p's gradient (None for a host-only context);
+        pull_dst(p) -> device pointer of its local weights; step(p, n) enqueues worker p's n-th
+        iteration (dssp_worker_step) or is None."""
+        self.ctx, self.K, self.d, self.quota = ctx, K, durations, quota
+        self.gp = grad_ptr or (lambda p: None)
+        self.pd = pull_dst or (lambda p: None)
+        self.step = step
+        self.log = [] if log else None
+        self.heap = []
+        self.pulled = [0] * K
+        self.count = [0] * K            # pushes so far per worker (mirror of the server's t)
+        self.version = 0
+        self.T_end = 0
+        for p in range(K):
+            v = B.dssp_pull(ctx, p, self.pd(p))
+            if log:
+                self.log.append((PULL, p, 0, 0, 0, 0, v, 0))
+            if step:
+                step(p, 0)
+            heapq.heappush(self.heap, (int(durations[p][0]), p))
+
+    def _start_next(self, q, T, tq, rq):
+        if self.quota is not None and tq >= self.quota:
+            return
+        v = B.dssp_pull(self.ctx, q, self.pd(q))
+        self.pulled[q] = v
+        if self.log is not None:
+            self.log.append((PULL, q, T, tq, rq, v, v, 0))
+        if self.step:
+            self.step(q, tq)
+        heapq.heappush(self.heap, (T + int(self.d[q][tq]), q))
+
+    def advance(self, n_pushes):
+        """Processes up to n_pushes pushes (fewer if every worker reached its quota).  Returns
+        the number processed."""
+        done = 0
+        K, log = self.K, self.log
+        while self.heap and done < n_pushes:
+            T, p = heapq.heappop(self.heap)
+            self.T_end = T
+            ok, released, rstar, grant = B.dssp_push(self.ctx, p, self.gp(p), T, K)
+            self.version += 1
+            self.count[p] += 1
+            done += 1
+            if log is not None:
+                t, r, _, v = B.dssp_clock(self.ctx, K)
+                log.append((PUSH, p, T, t[p], r[p], v, self.pulled[p], 0))
+                if rstar >= 0:
+                    log.append((CTRL, p, T, t[p], r[p], v, rstar, grant))
+                log.append((OK if ok else BLOCK, p, T, t[p], r[p], v, 0, 0))
+            else:
+                t, r = self.count, [0] * K
+            if ok:
+                self._start_next(p, T, t[p], r[p])
+            for q in released:
+                if log is not None:
+                    log.append((RELEASE, q, T, t[q], r[q], self.version, 0, 0))
+                self._start_next(q, T, t[q], r[q])
+        return done
+
+
 def run_schedule(ctx, K, durations, quota=None, total=None, grad_ptr=None, pull_dst=None, step=None, log=True):
-    """Runs the schedule.  grad_ptr(p) -> device pointer of worker p's gradient (None for a
-    host-only context); pull_dst(p) -> device pointer of its local weights; step(p, n) enqueues
-    worker p's n-th iteration (dssp_worker_step) or None.  Returns (log, stats)."""
+    """Runs a whole schedule: until `total` pushes were applied and / or every worker made
+    `quota` pushes.  Returns (log, stats)."""
     if quota is None and total is None:
         raise ValueError("need quota or total")
-    gp = grad_ptr or (lambda p: None)
-    pd = pull_dst or (lambda p: None)
-    out = [] if log else None
-    heap = []
-    pulled = [0] * K
-    count = [0] * K             # pushes so far per worker (mirror of the server's t)
-    version = 0
-    T_end = 0
-    for p in range(K):
-        v = B.dssp_pull(ctx, p, pd(p))
-        if log:
-            out.append((PULL, p, 0, 0, 0, 0, v, 0))
-        if step:
-            step(p, 0)
-        heapq.heappush(heap, (int(durations[p][0]), p))
-
-    def start_next(q, T, tq, rq):
-        if quota is not None and tq >= quota:
-            return
-        v = B.dssp_pull(ctx, q, pd(q))
-        pulled[q] = v
-        if log:
-            out.append((PULL, q, T, tq, rq, v, v, 0))
-        if step:
-            step(q, tq)
-        heapq.heappush(heap, (T + int(durations[q][tq]), q))
-
-    while heap and (total is None or version < total):
-        T, p = heapq.heappop(heap)
-        T_end = T
-        ok, released, rstar, grant = B.dssp_push(ctx, p, gp(p), T, K)
-        version += 1
-        count[p] += 1
-        if log:
-            t, r, _, v = B.dssp_clock(ctx, K)
-            out.append((PUSH, p, T, t[p], r[p], v, pulled[p], 0))
-            if rstar >= 0:
-                out.append((CTRL, p, T, t[p], r[p], v, rstar, grant))
-            out.append((OK if ok else BLOCK, p, T, t[p], r[p], v, 0, 0))
-        else:
-            t, r = count, [0] * K
-        if ok:
-            start_next(p, T, t[p], r[p])
-        for q in released:
-            if log:
-                out.append((RELEASE, q, T, t[q], r[q], version, 0, 0))
-            start_next(q, T, t[q], r[q])
-    return out, dict(T_end=T_end, pushes=version)
+    s = Schedule(ctx, K, durations, quota=quota, grad_ptr=grad_ptr, pull_dst=pull_dst, step=step, log=log)
+    s.advance(total if total is not None else K * quota)
+    return s.log, dict(T_end=s.T_end, pushes=s.version)

@@ -70,6 +70,11 @@ class Emulation:
                                   step=self.step, log=log)
         return out
 
+    def schedule(self, durations, quota=None, log=True):
+        """Resumable form of run(): returns a driver.Schedule (all workers pulled and started)."""
+        return driver.Schedule(self.ctx, self.K, durations, quota=quota, grad_ptr=lambda p: self.grad[p],
+                               pull_dst=lambda p: self.w_local[p], step=self.step, log=log)
+
     def synchronize(self):
         B.dssp_synchronize(self.ctx)
 

@@ -1,0 +1,130 @@
+"""CPU-side checks of the library: it loads, exports every symbol the headers declare, its host
+controller (Alg. 1 server part + Alg. 2) makes the oracle's decisions, and its parameter layout is
+the documented one.  No compute call is made (host-only contexts enqueue nothing)."""
+import os
+import random
+import re
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+from paper_1908_11848_amd import binding as B, driver, inputs
+from oracle import dssp_rules as R
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    names = set()
+    for h in ("dssp.h", "dssp_kernels.h"):
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(dsspk?_[a-z0-9_]+)\s*\(", text))
+    return names
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = B.lib()
+    names = declared_symbols()
+    assert len(names) >= 30
+    for n in names:
+        assert hasattr(lib, n), n
+    assert names == set(B._SIGNATURES), names ^ set(B._SIGNATURES)      # binding and headers list the same calls
+
+
+def host_log(K, s_L, r_max, d, quota=None, total=None):
+    ctx = B.dssp_create(None, 0, K, s_L, r_max, 0.1)
+    try:
+        return driver.run_schedule(ctx, K, d, quota=quota, total=total)[0]
+    finally:
+        B.dssp_destroy(ctx)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_host_controller_matches_oracle_random(seed):
+    rnd = random.Random(seed)
+    K = rnd.randint(1, 12)
+    s_L, r_max = rnd.choice([0, 1, 2, 3, 5]), rnd.choice([0, 1, 4, 12, 15])
+    g = np.random.default_rng(seed)
+    m = g.uniform(1.0, 4.0, K)
+    d = np.maximum((m[:, None] * np.exp(0.3 * g.standard_normal((K, 130))) * 1000).astype(np.int64), 1)
+    if seed % 4 == 0:
+        d[:, :] = d[:, :1]                       # constant intervals: many exact ties in Alg. 2
+    if seed % 5 == 0:
+        d[rnd.randrange(K), 40:] *= 12           # a straggler appears
+    quota = 120
+    olog, st, _ = R.simulate(K, s_L, r_max, d, quota=quota)
+    assert host_log(K, s_L, r_max, d, quota=quota) == olog
+
+
+@pytest.mark.parametrize("cfg,K,s_L,r_max,total", [(1, 4, 3, 4, 200), (2, 4, 3, 12, 400), (3, 4, 3, 12, 400),
+                                                   (3, 4, 0, 0, 400), (3, 4, 3, 0, 400), (3, 4, B.DSSP_S_L_NEVER_WAIT, 0, 400),
+                                                   (4, 8, 3, 12, 200), (5, 16, 3, 15, 10000)])
+def test_host_controller_matches_oracle_on_workload_schedules(cfg, K, s_L, r_max, total):
+    d = inputs.durations(cfg, K, total)
+    olog, _, _ = R.simulate(K, s_L, r_max, d, total=total)
+    assert host_log(K, s_L, r_max, d, total=total) == olog
+
+
+def test_clock_and_state_errors_host_only():
+    ctx = B.dssp_create(None, 0, 3, 1, 0, 0.1)
+    t, r, blocked, v = B.dssp_clock(ctx, 3)
+    assert (t, r, blocked, v) == ([0, 0, 0], [0, 0, 0], [False] * 3, 0)
+    for T in (10, 20):
+        ok, rel, rs, gr = B.dssp_push(ctx, 0, None, T, 3)
+        assert B.dssp_pull(ctx, 0, None) == (1 if T == 10 else 2) if ok else True
+    # t = [2,0,0], s_L = 1: worker 0 is 2 ahead -> it waits, the controller (r_max = 0) returned 0
+    t, r, blocked, v = B.dssp_clock(ctx, 3)
+    assert t == [2, 0, 0] and blocked == [True, False, False] and v == 2
+    with pytest.raises(B.DsspError) as e:
+        B.dssp_push(ctx, 0, None, 30, 3)
+    assert e.value.code == B.DSSP_ESTATE
+    with pytest.raises(B.DsspError) as e:
+        B.dssp_pull(ctx, 0, None)
+    assert e.value.code == B.DSSP_ESTATE
+    with pytest.raises(B.DsspError) as e:
+        B.dssp_pull(ctx, 3, None)
+    assert e.value.code == B.DSSP_EINVAL
+    ok, rel, _, _ = B.dssp_push(ctx, 1, None, 40, 3)
+    assert ok and rel == []
+    ok, rel, _, _ = B.dssp_push(ctx, 2, None, 41, 3)
+    assert ok and rel == [0]                     # slowest caught up to within s_L
+    B.dssp_destroy(ctx)
+    for bad in [(0, 0, 0), (2, -1, 0), (2, 0, -1)]:
+        with pytest.raises(B.DsspError):
+            B.dssp_create(None, 0, *bad, 0.1)
+
+
+def test_parameter_layout_matches_documented_one(oracle_nn):
+    for model, ncls, want in [("mlp", 10, 789_258), ("alexnet_ds", 10, 1_387_786), ("resnet110", 100, 1_733_812),
+                              ("resnet20", 100, None), ("resnet8", 7, None)]:
+        mid = B.model_id(model)
+        segs = B.dssp_model_segments(mid, ncls)
+        net = oracle_nn.make_net(model, ncls)
+        osegs = net.segments()
+        assert [s[1] for s in segs] == [int(np.prod(shape)) for _, shape in osegs]
+        for (kind, size, fan), (name, shape) in zip(segs, osegs):
+            suffix = name.rsplit(".", 1)[1]
+            assert kind == {"w": 0, "g": 2, "b": 3 if ".bn" in name else 1}[suffix]
+            if kind == 0:
+                assert fan == int(np.prod(shape[:-1]))
+        n = B.dssp_model_param_count(mid, ncls)
+        assert n == net.n_params() and (want is None or n == want)
+        assert B.dssp_workspace_bytes(mid, 8, ncls, 2) == 2 * B.dssp_workspace_bytes(mid, 8, ncls, 1) > 0
+    assert B.dssp_model_param_count(7, 10) < 0 and B.dssp_workspace_bytes(0, 8, 10, 2) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode != 0 and "ONE GPU" in (p.stderr + p.stdout)
+
+
+def test_oracle_is_not_imported_by_the_product():
+    pkg = os.path.join(ROOT, "paper_1908_11848_amd")
+    for fn in os.listdir(pkg):
+        if fn.endswith(".py"):
+            assert "oracle" not in open(os.path.join(pkg, fn)).read(), fn
+    for fn in os.listdir(os.path.join(pkg, "csrc")):
+        assert "oracle" not in open(os.path.join(pkg, "csrc", fn)).read(), fn
