@@ -59,7 +59,7 @@ int dsspk_maxpool_bwd(void* stream, const float* dy_dev, const uint8_t* arg_dev,
  * fwd: y = gamma*(x-mean)*invstd + beta (+ shortcut) (ReLU if relu).
  *   shortcut_mode 0: none; 1: sc_dev has y's shape; 2: sc_dev is [N][2Ho][2Wo][C/2], subsampled by
  *   2 in h and w, channels >= C/2 read as zero (Ho, Wo, N given by sc_n, sc_ho, sc_wo).
- * scratch_dev: dsspk_bn_scratch_floats(M, C) floats. */
+ * scratch_dev: dsspk_bn_scratch_floats(M, C) floats (per-slab partial results; one buffer serves one stream at a time). */
 int dsspk_bn_fwd(void* stream, const float* x_dev, const float* gamma_dev, const float* beta_dev, float* y_dev,
                  float* stats_dev, float* scratch_dev, long M, int C, float eps, int relu,
                  int shortcut_mode, const float* sc_dev, int sc_n, int sc_ho, int sc_wo);

@@ -13,6 +13,11 @@
 #include "mma.hpp"
 #include "../../include/dssp_kernels.h"
 
+// Specialised 3x3 / stride 1 / Cin = Cout kernels (k_conv3x3.hip); -2 = shape not covered.
+int conv3x3_direct(hipStream_t s, const float* src, const float* w, float* dst, int N, int HW, int C, bool transposed);
+int wgrad3x3_direct_parts(int N, int HW, int C);
+int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C);
+
 namespace {
 
 constexpr int THREADS = 256;
@@ -279,20 +284,37 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
     }
 }
 
-// d-filter, stage 2: dw[e] = sum over chunks of partial[chunk][e], chunks in ascending order
-// within each of 8 interleaved groups, groups combined pairwise in a fixed order.
+// d-filter, stage 2: dw[e] = sum over chunks of partial[chunk][e].  A workgroup owns 32 consecutive
+// elements (8 sixteen-byte columns) and splits the chunks over 32 row groups; every lane adds its
+// chunks in ascending order and the row groups are combined by a fixed tree.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dw,
                                                            int E, int chunks) {
-    __shared__ float part[8][32];
-    const int c = threadIdx.x & 31, gq = threadIdx.x >> 5;
-    const int e = blockIdx.x * 32 + c;
-    float s = 0.f;
+    __shared__ float4 part[32][8];
+    const int cg = threadIdx.x & 7, rg = threadIdx.x >> 3;
+    const int e = (blockIdx.x * 8 + cg) * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     if (e < E)
-        for (int k = gq; k < chunks; k += 8) s += partial[(long)k * E + e];
-    part[gq][c] = s;
+        for (int k = rg; k < chunks; k += 128) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = (k + 32 * u < chunks) ? *reinterpret_cast<const float4*>(partial + (long)(k + 32 * u) * E + e)
+                                             : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+        }
+    part[rg][cg] = s;
     __syncthreads();
-    if (gq == 0 && e < E)
-        dw[e] = ((part[0][c] + part[1][c]) + (part[2][c] + part[3][c])) + ((part[4][c] + part[5][c]) + (part[6][c] + part[7][c]));
+    for (int h = 16; h >= 1; h >>= 1) {
+        if (rg < h) {
+            float4 a = part[rg][cg];
+            const float4 b = part[rg + h][cg];
+            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            part[rg][cg] = a;
+        }
+        __syncthreads();
+    }
+    if (rg == 0 && e < E) *reinterpret_cast<float4*>(dw + e) = part[0][cg];
 }
 
 bool geom(ConvGeom& g, int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
@@ -334,6 +356,10 @@ extern "C" int dsspk_conv_fwd(void* stream, const float* x, const float* w, cons
                               int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad, int relu) {
     ConvGeom g;
     if (!x || !w || !y || !geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
+    if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W && !bias && !relu) {
+        const int rc = conv3x3_direct((hipStream_t)stream, x, w, y, N, H, Cin, false);
+        if (rc != -2) return rc;
+    }
     if (Cin % 16 == 0) return launch_igemm<false, true>((hipStream_t)stream, x, w, bias, y, g, relu);
     return launch_igemm<false, false>((hipStream_t)stream, x, w, bias, y, g, relu);
 }
@@ -343,6 +369,10 @@ extern "C" int dsspk_conv_bwd_data(void* stream, const float* dy, const float* w
     ConvGeom f;
     if (!dy || !w || !dx || !geom(f, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
     if (Cout % 16) return -1;
+    if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
+        const int rc = conv3x3_direct((hipStream_t)stream, dy, w, dx, N, H, Cin, true);
+        if (rc != -2) return rc;
+    }
     ConvGeom g = f;                       // rows: input pixels; gathered tensor: dy
     g.OH = H; g.OW = W; g.SH = f.OH; g.SW = f.OW; g.IC = Cout; g.OC = Cin;
     g.M = (long)N * H * W;
@@ -354,7 +384,11 @@ extern "C" size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, 
     if (!geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return 0;
     const int gy = (Cin % 16 == 0) ? KH * KW : 1;
     const int stages = wgrad_stages(g, gy);
-    const long chunks = ceil_div(g.M, 64L * stages);
+    long chunks = ceil_div(g.M, 64L * stages);
+    if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
+        const long parts = wgrad3x3_direct_parts(N, H, Cin);
+        if (parts > chunks) chunks = parts;
+    }
     return (size_t)chunks * KH * KW * Cin * Cout;
 }
 
@@ -366,6 +400,16 @@ extern "C" int dsspk_conv_bwd_weight(void* stream, const float* x, const float* 
     hipStream_t s = (hipStream_t)stream;
     const bool vec = Cin % 16 == 0;
     const int rows_total = KH * KW * Cin;
+    if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
+        const int parts = wgrad3x3_direct_parts(N, H, Cin);
+        if (parts > 0) {
+            int rc = wgrad3x3_direct(s, x, dy, scratch, N, H, Cin);
+            if (rc) return rc;
+            const int E = rows_total * Cout;
+            hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(ceil_div(E, 32)), dim3(256), 0, s, scratch, dw, E, parts);
+            return DSSPK_LAUNCH_RC();
+        }
+    }
     const int gy = vec ? KH * KW : 1;
     const int stages = wgrad_stages(g, gy);
     const int chunks = ceil_div(g.M, 64L * stages);

@@ -1,0 +1,279 @@
+// 3x3, stride 1, pad 1 convolutions with Cin = Cout = C (the 106 inner convolutions of
+// ResNet-110): forward and gradient w.r.t. the input as ONE kernel.
+//
+// A workgroup owns a band of R output rows of one image (the whole 8x8 image in the last
+// stage) and CN of the C output channels.  It loads the (R+2) x (HW+2) x C input halo tile
+// (zero borders) and its 9 x C x CN filter slab into LDS once; all nine taps are then served
+// from LDS, so every input element is read from memory once per band instead of nine times.
+// Matrix-core tiles are 16 pixels (a run along the image row; two 8-pixel rows in the last
+// stage) x 16 output channels, v_mfma_f32_16x16x4_f32, with the k-permutation of mma.hpp: both
+// operands are k-contiguous in LDS, so each lane feeds four MFMAs from one 16-byte read per
+// operand.
+//
+// Gradient w.r.t. the input of such a convolution is the same operation on dy with the filter
+// taps reversed and its two channel indices swapped; only the filter load differs.
+#include "mma.hpp"
+#include "../../include/dssp_kernels.h"
+
+namespace {
+
+constexpr int THREADS = 256;
+
+template <int C, int HW, int R, int NSPLIT>
+struct Cfg {
+    static constexpr int CN = C / NSPLIT;          // output channels per workgroup
+    static constexpr int LDC = C + 4;              // pitch of one pixel / one filter row in LDS (floats)
+    static constexpr int TW = HW + 2;              // halo tile width
+    static constexpr int XS = (R + 2) * TW * LDC;  // floats
+    static constexpr int WS = 9 * CN * LDC;        // filter slab [tap][co][ci], ci contiguous
+    static constexpr int RUNS = R * HW / 16;       // 16-pixel runs in the band
+    static constexpr int WM = RUNS / 4;            // runs per wavefront
+    static constexpr int WN = CN / 16;
+    static constexpr size_t LDS_BYTES = (size_t)(XS + WS) * sizeof(float);
+    static_assert(RUNS % 4 == 0 && WM >= 1, "band must give every wavefront at least one run");
+};
+
+template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED>
+__global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
+                                                          float* __restrict__ dst) {
+    using K = Cfg<C, HW, R, NSPLIT>;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float* Xs = lds;
+    float* Ws = lds + K::XS;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int BANDS = HW / R;
+    const int split = blockIdx.x % NSPLIT;
+    const int band = (blockIdx.x / NSPLIT) % BANDS;
+    const int n = blockIdx.x / (NSPLIT * BANDS);
+    const int r_base = band * R;                    // first output row of the band
+    const int co_base = split * K::CN;
+
+    // ---- input halo tile, zero outside the image
+    constexpr int V = C / 4;
+    for (int idx = tid; idx < (R + 2) * K::TW * V; idx += THREADS) {
+        const int v = idx % V;
+        const int pc = (idx / V) % K::TW, pr = idx / (V * K::TW);
+        const int h = r_base + pr - 1, w = pc - 1;
+        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (h >= 0 && h < HW && w >= 0 && w < HW)
+            val = *reinterpret_cast<const float4*>(src + (((long)n * HW + h) * HW + w) * C + 4 * v);
+        *reinterpret_cast<float4*>(&Xs[(pr * K::TW + pc) * K::LDC + 4 * v]) = val;
+    }
+    // ---- filter slab Ws[tap][j][k]: j = output channel of this kernel, k = reduction channel.
+    //      forward : Ws[tap][co][ci] = w[tap][ci][co]          (transposing store)
+    //      d-input : Ws[tap][ci][co] = w[8 - tap][ci][co]      (straight copy, taps reversed)
+    if constexpr (!TRANSPOSED) {
+        for (int idx = tid; idx < 9 * C * (K::CN / 4); idx += THREADS) {
+            const int j4 = idx % (K::CN / 4);
+            const int k = (idx / (K::CN / 4)) % C, tap = idx / ((K::CN / 4) * C);
+            const float4 val = *reinterpret_cast<const float4*>(wgt + ((long)tap * C + k) * C + co_base + 4 * j4);
+            float* o = &Ws[(tap * K::CN + 4 * j4) * K::LDC + k];
+            o[0] = val.x; o[K::LDC] = val.y; o[2 * K::LDC] = val.z; o[3 * K::LDC] = val.w;
+        }
+    } else {
+        for (int idx = tid; idx < 9 * K::CN * V; idx += THREADS) {
+            const int v = idx % V;
+            const int j = (idx / V) % K::CN, tap = idx / (V * K::CN);
+            const float4 val = *reinterpret_cast<const float4*>(wgt + ((long)(8 - tap) * C + co_base + j) * C + 4 * v);
+            *reinterpret_cast<float4*>(&Ws[(tap * K::CN + j) * K::LDC + 4 * v]) = val;
+        }
+    }
+    __syncthreads();
+
+    // ---- 9 taps x C/16 k-chunks from LDS
+    floatx4 acc[K::WM][K::WN];
+    mma::zero(acc);
+    const int l16 = lane & 15, q = lane >> 4;
+    int pix_off[K::WM];                             // LDS offset of this lane's pixel for tap (0,0)
+#pragma unroll
+    for (int wm = 0; wm < K::WM; ++wm) {
+        const int run = wave * K::WM + wm;
+        const int p = run * 16 + l16;               // pixel index inside the band, row-major
+        pix_off[wm] = ((p / HW) * K::TW + (p % HW)) * K::LDC + 4 * q;
+    }
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+        const int toff = ((tap / 3) * K::TW + (tap % 3)) * K::LDC;
+#pragma unroll
+        for (int kc = 0; kc < C / 16; ++kc) {
+            float4 a[K::WM], b[K::WN];
+#pragma unroll
+            for (int wm = 0; wm < K::WM; ++wm)
+                a[wm] = *reinterpret_cast<const float4*>(&Xs[pix_off[wm] + toff + 16 * kc]);
+#pragma unroll
+            for (int wn = 0; wn < K::WN; ++wn)
+                b[wn] = *reinterpret_cast<const float4*>(&Ws[(tap * K::CN + 16 * wn + l16) * K::LDC + 16 * kc + 4 * q]);
+#pragma unroll
+            for (int wm = 0; wm < K::WM; ++wm)
+#pragma unroll
+                for (int wn = 0; wn < K::WN; ++wn) {
+                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].x, b[wn].x, acc[wm][wn], 0, 0, 0);
+                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].y, b[wn].y, acc[wm][wn], 0, 0, 0);
+                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].z, b[wn].z, acc[wm][wn], 0, 0, 0);
+                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].w, b[wn].w, acc[wm][wn], 0, 0, 0);
+                }
+        }
+    }
+
+    // ---- store: lane holds rows 4q..4q+3 (pixels of the run) of column l16
+#pragma unroll
+    for (int wm = 0; wm < K::WM; ++wm) {
+        const int run = wave * K::WM + wm;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int p = run * 16 + 4 * q + v;
+            const int h = r_base + p / HW, w = p % HW;
+            float* o = dst + (((long)n * HW + h) * HW + w) * C + co_base + l16;
+#pragma unroll
+            for (int wn = 0; wn < K::WN; ++wn) o[16 * wn] = acc[wm][wn][v];
+        }
+    }
+}
+
+template <int C, int HW, int R, int NSPLIT, bool T>
+int launch(hipStream_t s, const float* src, const float* w, float* dst, int N) {
+    using K = Cfg<C, HW, R, NSPLIT>;
+    static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
+    auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T>;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)K::LDS_BYTES) != hipSuccess)
+            return -1;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, dst);
+    return DSSPK_LAUNCH_RC();
+}
+
+}  // namespace
+
+// Returns -2 if the shape is not one of the specialised ones (the caller then uses the generic kernel).
+int conv3x3_direct(hipStream_t s, const float* src, const float* w, float* dst, int N, int HW, int C, bool transposed) {
+    if (C == 16 && HW == 32) return transposed ? launch<16, 32, 8, 1, true>(s, src, w, dst, N) : launch<16, 32, 8, 1, false>(s, src, w, dst, N);
+    if (C == 32 && HW == 16) return transposed ? launch<32, 16, 8, 1, true>(s, src, w, dst, N) : launch<32, 16, 8, 1, false>(s, src, w, dst, N);
+    if (C == 64 && HW == 8) return transposed ? launch<64, 8, 8, 2, true>(s, src, w, dst, N) : launch<64, 8, 8, 2, false>(s, src, w, dst, N);
+    return -2;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gradient w.r.t. the filter of the same convolutions, stage 1 of 2: one workgroup per band of
+// R rows of one image; the x halo tile and the dy tile sit in LDS and all nine taps
+//   dw[tap][ci][co] += sum_{pixels of the band} x[pixel + tap][ci] * dy[pixel][co]
+// are accumulated from them (x and dy are read from memory once).  The matrix-core tile is
+// 16 (ci) x 16 (co), the reduction runs over pixels in chunks of 16.
+//   C = 16: one tile per tap; the four wavefronts split the pixel chunks and are summed in a
+//           fixed order at the end.
+//   C = 32: four tiles per tap; wavefront w owns tile (w / 2, w % 2) and walks all pixels.
+// Output: partial[workgroup][tap][ci][co]; stage 2 (wgrad_reduce_kernel) sums over workgroups.
+namespace {
+
+template <int C, int HW, int R>
+struct WCfg {
+    static constexpr int LDC = C + 4;
+    static constexpr int TW = HW + 2;
+    static constexpr int XS = (R + 2) * TW * LDC;
+    static constexpr int DS = R * HW * LDC;
+    static constexpr int CHUNKS = R * HW / 16;
+    static constexpr bool SPLIT_K = (C == 16);
+    static constexpr int RED = SPLIT_K ? 4 * 9 * C * C : 0;
+    static constexpr size_t LDS_BYTES = (size_t)((XS + DS) > RED ? (XS + DS) : RED) * sizeof(float);
+};
+
+template <int C, int HW, int R>
+__global__ __launch_bounds__(THREADS) void wgrad3x3_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                           float* __restrict__ partial) {
+    using K = WCfg<C, HW, R>;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float* Xs = lds;
+    float* Ds = lds + K::XS;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int BANDS = HW / R;
+    const int band = blockIdx.x % BANDS, n = blockIdx.x / BANDS;
+    const int r_base = band * R;
+    constexpr int V = C / 4;
+    for (int idx = tid; idx < (R + 2) * K::TW * V; idx += THREADS) {
+        const int v = idx % V;
+        const int pc = (idx / V) % K::TW, pr = idx / (V * K::TW);
+        const int h = r_base + pr - 1, w = pc - 1;
+        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (h >= 0 && h < HW && w >= 0 && w < HW)
+            val = *reinterpret_cast<const float4*>(x + (((long)n * HW + h) * HW + w) * C + 4 * v);
+        *reinterpret_cast<float4*>(&Xs[(pr * K::TW + pc) * K::LDC + 4 * v]) = val;
+    }
+    const float* dyb = dy + ((long)n * HW + r_base) * HW * C;
+    for (int idx = tid; idx < R * HW * V; idx += THREADS) {
+        const int v = idx % V, p = idx / V;
+        *reinterpret_cast<float4*>(&Ds[p * K::LDC + 4 * v]) = *reinterpret_cast<const float4*>(dyb + (long)p * C + 4 * v);
+    }
+    __syncthreads();
+
+    const int l16 = lane & 15, q = lane >> 4;
+    const int cit = K::SPLIT_K ? 0 : wave >> 1, cot = K::SPLIT_K ? 0 : wave & 1;
+    floatx4 acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int c = K::SPLIT_K ? wave : 0; c < K::CHUNKS; c += K::SPLIT_K ? 4 : 1) {
+        float b[4];
+        int xo[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int p = 16 * c + 4 * q + s;
+            b[s] = Ds[p * K::LDC + 16 * cot + l16];
+            xo[s] = ((p / HW) * K::TW + (p % HW)) * K::LDC + 16 * cit + l16;
+        }
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int toff = ((t / 3) * K::TW + (t % 3)) * K::LDC;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Xs[xo[s] + toff], b[s], acc[t], 0, 0, 0);
+        }
+    }
+    float* out = partial + (long)blockIdx.x * 9 * C * C;
+    if constexpr (K::SPLIT_K) {
+        __syncthreads();                              // tiles no longer needed: reuse LDS for the 4 partial sums
+        float* Red = lds;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Red[wave * 9 * C * C + (t * C + 4 * q + v) * C + l16] = acc[t][v];
+        __syncthreads();
+        for (int idx = tid; idx < 9 * C * C; idx += THREADS)
+            out[idx] = (Red[idx] + Red[9 * C * C + idx]) + (Red[2 * 9 * C * C + idx] + Red[3 * 9 * C * C + idx]);
+    } else {
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) out[(t * C + 16 * cit + 4 * q + v) * C + 16 * cot + l16] = acc[t][v];
+    }
+}
+
+template <int C, int HW, int R>
+int launch_wgrad(hipStream_t s, const float* x, const float* dy, float* partial, int N) {
+    using K = WCfg<C, HW, R>;
+    static bool attr_set = false;
+    auto kern = wgrad3x3_kernel<C, HW, R>;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)K::LDS_BYTES) != hipSuccess)
+            return -1;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(N * (HW / R)), dim3(THREADS), K::LDS_BYTES, s, x, dy, partial);
+    return DSSPK_LAUNCH_RC();
+}
+
+}  // namespace
+
+// Number of partial results (workgroups) the specialised d-filter kernel writes, 0 if the shape is not covered.
+int wgrad3x3_direct_parts(int N, int HW, int C) {
+    if (C == 16 && HW == 32) return N * 4;
+    if (C == 32 && HW == 16) return N * 2;
+    return 0;
+}
+
+int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C) {
+    if (C == 16 && HW == 32) return launch_wgrad<16, 32, 8>(s, x, dy, partial, N);
+    if (C == 32 && HW == 16) return launch_wgrad<32, 16, 8>(s, x, dy, partial, N);
+    return -2;
+}

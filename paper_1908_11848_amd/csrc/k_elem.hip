@@ -88,18 +88,24 @@ __global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const float* __res
 }
 
 // ------------------------------------------------------------------ batch normalisation
+// Two kernels per direction, no cross-workgroup synchronisation:
+//   forward : (1) per slab of rows, mean and sum of squared deviations per channel;
+//             (2) every workgroup of the apply kernel merges the (at most 128) slab results in
+//                 its prologue - identical arithmetic in every workgroup - then normalises.
+//   backward: (1) per slab, sum dz and sum dz*xhat (ReLU mask applied, dz written back);
+//             (2) every workgroup of the dx kernel sums the slab results in its prologue.
 struct BnLayout {
     int VC, RL;          // 16-byte columns per row, row lanes per workgroup
     long rows_per_block;
-    int G;               // workgroups / partial results
+    int G;               // slabs = workgroups of the partial kernels
 };
 
 __host__ __device__ inline BnLayout bn_layout(long M, int C) {
     BnLayout L;
     L.VC = C / 4;
     L.RL = THREADS / L.VC;
-    long rpb = (M + 511) / 512;                     // at most 512 partials
-    if (rpb < 256) rpb = 256;
+    long rpb = (M + 127) / 128;                     // at most 128 slabs
+    if (rpb < 64) rpb = 64;
     rpb = (rpb + L.RL - 1) / L.RL * L.RL;
     L.rows_per_block = rpb;
     L.G = (int)((M + rpb - 1) / rpb);
@@ -136,11 +142,17 @@ __global__ __launch_bounds__(THREADS) void bn_stats_partial_kernel(const float* 
     const long r1 = min(M, r0 + L.rows_per_block);
     const float4 pivot = *reinterpret_cast<const float4*>(x + r0 * C + 4 * vc);
     float4 s1 = make_float4(0.f, 0.f, 0.f, 0.f), s2 = s1;
-    for (long r = r0 + rl; r < r1; r += L.RL) {
-        const float4 v = *reinterpret_cast<const float4*>(x + r * C + 4 * vc);
-        const float dx_ = v.x - pivot.x, dy_ = v.y - pivot.y, dz_ = v.z - pivot.z, dw_ = v.w - pivot.w;
-        s1.x += dx_; s1.y += dy_; s1.z += dz_; s1.w += dw_;
-        s2.x = fmaf(dx_, dx_, s2.x); s2.y = fmaf(dy_, dy_, s2.y); s2.z = fmaf(dz_, dz_, s2.z); s2.w = fmaf(dw_, dw_, s2.w);
+    for (long r = r0 + rl; r < r1; r += 4 * L.RL) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)            // four independent loads in flight; rows past the slab read as the pivot (adds 0)
+            v[u] = (r + u * L.RL < r1) ? *reinterpret_cast<const float4*>(x + (r + u * L.RL) * C + 4 * vc) : pivot;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float dx_ = v[u].x - pivot.x, dy_ = v[u].y - pivot.y, dz_ = v[u].z - pivot.z, dw_ = v[u].w - pivot.w;
+            s1.x += dx_; s1.y += dy_; s1.z += dz_; s1.w += dw_;
+            s2.x = fmaf(dx_, dx_, s2.x); s2.y = fmaf(dy_, dy_, s2.y); s2.z = fmaf(dz_, dz_, s2.z); s2.w = fmaf(dw_, dw_, s2.w);
+        }
     }
     s1 = reduce_rows(s1, red, rl, vc, L.RL, L.VC);
     s2 = reduce_rows(s2, red, rl, vc, L.RL, L.VC);
@@ -167,11 +179,10 @@ __device__ __forceinline__ float reduce_sub(float v, float* red, int c, int sub,
     return out;
 }
 
-// Combine the slab results: mean = sum n_g mean_g / M, M2 = sum (M2_g + n_g (mean_g - mean)^2).
-// stats[c] = mean, stats[C + c] = 1 / sqrt(M2 / M + eps).  One workgroup, THREADS / C lanes per channel.
-__global__ __launch_bounds__(THREADS) void bn_stats_final_kernel(const float* __restrict__ partial, float* __restrict__ stats,
-                                                                 long M, int C, float eps) {
-    __shared__ float red[THREADS];
+// Merge of the slab results by the whole workgroup (THREADS / C lanes per channel):
+// mean = sum n_g mean_g / M, M2 = sum (M2_g + n_g (mean_g - mean)^2).
+// On return sh[c] = mean, sh[C + c] = 1 / sqrt(M2 / M + eps) for every channel.
+__device__ __forceinline__ void bn_merge_stats(const float* __restrict__ partial, long M, int C, float eps, float* red, float* sh) {
     const BnLayout L = bn_layout(M, C);
     const int SUB = THREADS / C;
     const int c = threadIdx.x % C, sub = threadIdx.x / C;
@@ -189,25 +200,31 @@ __global__ __launch_bounds__(THREADS) void bn_stats_final_kernel(const float* __
     }
     m2 = reduce_sub(m2, red, c, sub, SUB, C);
     if (sub == 0) {
-        stats[c] = mean;
-        stats[C + c] = 1.0f / sqrtf(m2 / (float)M + eps);
+        sh[c] = mean;
+        sh[C + c] = 1.0f / sqrtf(m2 / (float)M + eps);
     }
+    __syncthreads();
 }
 
-// y = gamma * (x - mean) * invstd + beta (+ shortcut) (ReLU)
+// y = gamma * (x - mean) * invstd + beta (+ shortcut) (ReLU); workgroup 0 also stores mean / invstd
+// to stats[] for the backward pass.
 template <int SC_MODE>
 __global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restrict__ x, const float* __restrict__ gamma,
-                                                           const float* __restrict__ beta, const float* __restrict__ stats,
-                                                           float* __restrict__ y, long M, int C, int relu,
-                                                           const float* __restrict__ sc, int sc_ho, int sc_wo) {
+                                                           const float* __restrict__ beta, const float* __restrict__ partial,
+                                                           float* __restrict__ stats, float* __restrict__ y, long M, int C,
+                                                           float eps, int relu, const float* __restrict__ sc, int sc_ho, int sc_wo) {
+    __shared__ float red[THREADS];
+    __shared__ __attribute__((aligned(16))) float sh[2 * THREADS];
+    bn_merge_stats(partial, M, C, eps, red, sh);
+    if (blockIdx.x == 0 && threadIdx.x < 2 * C) stats[threadIdx.x] = sh[threadIdx.x];
     const int VC = C / 4;
     const long total = M * VC;
     for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < total; i += (long)gridDim.x * THREADS) {
         const int vc = (int)(i % VC);
         const long row = i / VC;
         const float4 v = *reinterpret_cast<const float4*>(x + row * C + 4 * vc);
-        const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
-        const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
+        const float4 mu = *reinterpret_cast<const float4*>(sh + 4 * vc);
+        const float4 is = *reinterpret_cast<const float4*>(sh + C + 4 * vc);
         const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
         const float4 be = *reinterpret_cast<const float4*>(beta + 4 * vc);
         float4 o;
@@ -246,20 +263,31 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_partial_kernel(const float* __
     const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
     const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
     float4 sb = make_float4(0.f, 0.f, 0.f, 0.f), sg = sb;
-    for (long r = r0 + rl; r < r1; r += L.RL) {
-        float4 d = *reinterpret_cast<const float4*>(da + r * C + 4 * vc);
-        if (out) {
-            const float4 o = *reinterpret_cast<const float4*>(out + r * C + 4 * vc);
-            d.x = o.x > 0.f ? d.x : 0.f; d.y = o.y > 0.f ? d.y : 0.f;
-            d.z = o.z > 0.f ? d.z : 0.f; d.w = o.w > 0.f ? d.w : 0.f;
-            *reinterpret_cast<float4*>(da + r * C + 4 * vc) = d;
+    for (long r0u = r0 + rl; r0u < r1; r0u += 2 * L.RL) {
+        float4 d[2], v[2], o[2];
+        bool ok[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {           // two rows in flight per lane
+            const long r = r0u + u * L.RL;
+            ok[u] = r < r1;
+            d[u] = ok[u] ? *reinterpret_cast<const float4*>(da + r * C + 4 * vc) : make_float4(0.f, 0.f, 0.f, 0.f);
+            v[u] = ok[u] ? *reinterpret_cast<const float4*>(x + r * C + 4 * vc) : mu;
+            o[u] = (ok[u] && out) ? *reinterpret_cast<const float4*>(out + r * C + 4 * vc) : make_float4(1.f, 1.f, 1.f, 1.f);
         }
-        const float4 v = *reinterpret_cast<const float4*>(x + r * C + 4 * vc);
-        sb.x += d.x; sb.y += d.y; sb.z += d.z; sb.w += d.w;
-        sg.x = fmaf(d.x, (v.x - mu.x) * is.x, sg.x);
-        sg.y = fmaf(d.y, (v.y - mu.y) * is.y, sg.y);
-        sg.z = fmaf(d.z, (v.z - mu.z) * is.z, sg.z);
-        sg.w = fmaf(d.w, (v.w - mu.w) * is.w, sg.w);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const long r = r0u + u * L.RL;
+            if (out) {
+                d[u].x = o[u].x > 0.f ? d[u].x : 0.f; d[u].y = o[u].y > 0.f ? d[u].y : 0.f;
+                d[u].z = o[u].z > 0.f ? d[u].z : 0.f; d[u].w = o[u].w > 0.f ? d[u].w : 0.f;
+                if (ok[u]) *reinterpret_cast<float4*>(da + r * C + 4 * vc) = d[u];
+            }
+            sb.x += d[u].x; sb.y += d[u].y; sb.z += d[u].z; sb.w += d[u].w;
+            sg.x = fmaf(d[u].x, (v[u].x - mu.x) * is.x, sg.x);
+            sg.y = fmaf(d[u].y, (v[u].y - mu.y) * is.y, sg.y);
+            sg.z = fmaf(d[u].z, (v[u].z - mu.z) * is.z, sg.z);
+            sg.w = fmaf(d[u].w, (v[u].w - mu.w) * is.w, sg.w);
+        }
     }
     sb = reduce_rows(sb, red, rl, vc, L.RL, L.VC);
     sg = reduce_rows(sg, red, rl, vc, L.RL, L.VC);
@@ -269,27 +297,31 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_partial_kernel(const float* __
     }
 }
 
-__global__ __launch_bounds__(THREADS) void bn_bwd_final_kernel(const float* __restrict__ partial, float* __restrict__ dgamma,
-                                                               float* __restrict__ dbeta, long M, int C) {
-    __shared__ float red[THREADS];
-    const BnLayout L = bn_layout(M, C);
-    const int SUB = THREADS / C;
-    const int c = threadIdx.x % C, sub = threadIdx.x / C;
-    float sb = 0.f, sg = 0.f;
-    for (int g = sub; g < L.G; g += SUB) {
-        sb += partial[((long)g * C + c) * 2];
-        sg += partial[((long)g * C + c) * 2 + 1];
-    }
-    sb = reduce_sub(sb, red, c, sub, SUB, C);
-    sg = reduce_sub(sg, red, c, sub, SUB, C);
-    if (sub == 0) { dbeta[c] = sb; dgamma[c] = sg; }
-}
-
-// dx = gamma * invstd * (dz - dbeta / M - xhat * dgamma / M)
+// dx = gamma * invstd * (dz - dbeta / M - xhat * dgamma / M); dbeta = sum dz and dgamma = sum dz*xhat are
+// summed from the slab results by every workgroup (same order everywhere); workgroup 0 stores them.
 __global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restrict__ x, const float* __restrict__ gamma,
                                                             const float* __restrict__ stats, const float* __restrict__ dz,
-                                                            const float* __restrict__ dgamma, const float* __restrict__ dbeta,
-                                                            float* __restrict__ dx, long M, int C) {
+                                                            const float* __restrict__ partial, float* __restrict__ dgamma,
+                                                            float* __restrict__ dbeta, float* __restrict__ dx, long M, int C) {
+    __shared__ float red[THREADS];
+    __shared__ __attribute__((aligned(16))) float sh[2 * THREADS];      // [0,C): dbeta, [C,2C): dgamma
+    {
+        const BnLayout L = bn_layout(M, C);
+        const int SUB = THREADS / C;
+        const int c = threadIdx.x % C, sub = threadIdx.x / C;
+        float sb = 0.f, sg = 0.f;
+        for (int g = sub; g < L.G; g += SUB) {
+            sb += partial[((long)g * C + c) * 2];
+            sg += partial[((long)g * C + c) * 2 + 1];
+        }
+        sb = reduce_sub(sb, red, c, sub, SUB, C);
+        sg = reduce_sub(sg, red, c, sub, SUB, C);
+        if (sub == 0) {
+            sh[c] = sb; sh[C + c] = sg;
+            if (blockIdx.x == 0) { dbeta[c] = sb; dgamma[c] = sg; }
+        }
+        __syncthreads();
+    }
     const int VC = C / 4;
     const long total = M * VC;
     const float inv_m = 1.0f / (float)M;
@@ -301,8 +333,8 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restr
         const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
         const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
         const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
-        const float4 dg = *reinterpret_cast<const float4*>(dgamma + 4 * vc);
-        const float4 db = *reinterpret_cast<const float4*>(dbeta + 4 * vc);
+        const float4 db = *reinterpret_cast<const float4*>(sh + 4 * vc);
+        const float4 dg = *reinterpret_cast<const float4*>(sh + C + 4 * vc);
         float4 o;
         o.x = ga.x * is.x * (d.x - db.x * inv_m - (v.x - mu.x) * is.x * (dg.x * inv_m));
         o.y = ga.y * is.y * (d.y - db.y * inv_m - (v.y - mu.y) * is.y * (dg.y * inv_m));
@@ -415,6 +447,10 @@ extern "C" size_t dsspk_bn_scratch_floats(long M, int C) {
     return (size_t)bn_layout(M, C).G * C * 2;
 }
 
+// Workgroups of the elementwise BN kernels: each one repeats the merge of the slab results, so keep
+// their number moderate and let them stride over the rows.
+inline int bn_elem_grid(long M, int C) { return stream_grid(ceil_div(M * (C / 4), THREADS * 4L), 1024); }
+
 extern "C" int dsspk_bn_fwd(void* stream, const float* x, const float* gamma, const float* beta, float* y,
                             float* stats, float* scratch, long M, int C, float eps, int relu,
                             int shortcut_mode, const float* sc, int sc_n, int sc_ho, int sc_wo) {
@@ -425,27 +461,25 @@ extern "C" int dsspk_bn_fwd(void* stream, const float* x, const float* gamma, co
     hipStream_t s = (hipStream_t)stream;
     const BnLayout L = bn_layout(M, C);
     hipLaunchKernelGGL(bn_stats_partial_kernel, dim3(L.G), dim3(THREADS), 0, s, x, scratch, M, C);
-    hipLaunchKernelGGL(bn_stats_final_kernel, dim3(1), dim3(THREADS), 0, s, scratch, stats, M, C, eps);
-    const int grid = grid_for(M * (C / 4));
+    const int grid = bn_elem_grid(M, C);
     if (shortcut_mode == 0)
-        hipLaunchKernelGGL((bn_apply_kernel<0>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, stats, y, M, C, relu, sc, sc_ho, sc_wo);
+        hipLaunchKernelGGL((bn_apply_kernel<0>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo);
     else if (shortcut_mode == 1)
-        hipLaunchKernelGGL((bn_apply_kernel<1>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, stats, y, M, C, relu, sc, sc_ho, sc_wo);
+        hipLaunchKernelGGL((bn_apply_kernel<1>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo);
     else
-        hipLaunchKernelGGL((bn_apply_kernel<2>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, stats, y, M, C, relu, sc, sc_ho, sc_wo);
+        hipLaunchKernelGGL((bn_apply_kernel<2>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo);
     return DSSPK_LAUNCH_RC();
 }
 
 extern "C" int dsspk_bn_bwd(void* stream, const float* x, const float* gamma, const float* stats, float* da,
                             const float* out, float* dx, float* dgamma, float* dbeta, float* scratch, long M, int C) {
     if (!x || !gamma || !stats || !da || !dx || !dgamma || !dbeta || !scratch || !bn_ok(M, C)) return -1;
-    if (!al16(x) || !al16(da) || !al16(dx) || !al16(gamma) || !al16(stats) || !al16(dgamma) || !al16(dbeta)) return -1;
+    if (!al16(x) || !al16(da) || !al16(dx) || !al16(gamma) || !al16(stats)) return -1;
     if (out && !al16(out)) return -1;
     hipStream_t s = (hipStream_t)stream;
     const BnLayout L = bn_layout(M, C);
     hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3(L.G), dim3(THREADS), 0, s, x, stats, da, out, scratch, M, C);
-    hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(1), dim3(THREADS), 0, s, scratch, dgamma, dbeta, M, C);
-    hipLaunchKernelGGL(bn_bwd_dx_kernel, dim3(grid_for(M * (C / 4))), dim3(THREADS), 0, s, x, gamma, stats, da, dgamma, dbeta, dx, M, C);
+    hipLaunchKernelGGL(bn_bwd_dx_kernel, dim3(bn_elem_grid(M, C)), dim3(THREADS), 0, s, x, gamma, stats, da, scratch, dgamma, dbeta, dx, M, C);
     return DSSPK_LAUNCH_RC();
 }
 
