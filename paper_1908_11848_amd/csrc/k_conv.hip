@@ -284,6 +284,106 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
     }
 }
 
+// d-filter, stage 1, for wide layers (at least four 16x16 tiles per tap).  Same work split over
+// (pixel chunk, tap) workgroups, but each wavefront owns a block of the Cin x Cout result and walks
+// all 64 pixels of every slice (no cross-wavefront sum), and the next slice is prefetched into
+// registers while the matrix cores work on the current one (two LDS buffers, one barrier per slice).
+template <int CI_T, int CO_T>
+__global__ __launch_bounds__(THREADS) void conv_wgrad_tile_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                                  float* __restrict__ partial, ConvGeom g, int stages) {
+    constexpr int CIP = 16 * CI_T, COP = 16 * CO_T;
+    constexpr int LDA = CIP + 4, LDB = COP + 4;
+    constexpr int PIX = 64;
+    constexpr int WR = CI_T >= 2 ? 2 : 1, WC = 4 / WR;           // wavefront grid over the result
+    constexpr int TM = CI_T / WR, TN = CO_T / WC;                // tiles per wavefront
+    static_assert(CI_T % WR == 0 && CO_T % WC == 0 && TM >= 1 && TN >= 1, "tile split");
+    constexpr int XV = PIX * (CIP / 4) / THREADS, DV = PIX * (COP / 4) / THREADS;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float* Xs = lds;                                   // [2][PIX * LDA]
+    float* Ds = lds + 2 * PIX * LDA;                   // [2][PIX * LDB]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tap = blockIdx.y;
+    const int kh = tap / g.KW, kw = tap - kh * g.KW;
+    const long p_begin = (long)blockIdx.x * stages * PIX;
+    int nst = stages;
+    if (p_begin + (long)nst * PIX > g.M) nst = (int)((g.M - p_begin + PIX - 1) / PIX);
+
+    floatx4 acc[TM][TN];
+    mma::zero(acc);
+    float4 rx[XV], rd[DV];
+    auto load = [&](int st) {
+        const long p0 = p_begin + (long)st * PIX;
+#pragma unroll
+        for (int e = 0; e < XV; ++e) {
+            const int idx = tid + e * THREADS;
+            const int pix = idx / (CIP / 4), c4 = idx % (CIP / 4);
+            const long m = p0 + pix;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m < g.M) {
+                const int ow = (int)(m % g.OW), oh = (int)((m / g.OW) % g.OH), n = (int)(m / ((long)g.OW * g.OH));
+                int sh, sw;
+                if (src_pixel<false>(g, oh, ow, kh, kw, sh, sw))
+                    v = *reinterpret_cast<const float4*>(x + (((long)n * g.SH + sh) * g.SW + sw) * g.IC + 4 * c4);
+            }
+            rx[e] = v;
+        }
+#pragma unroll
+        for (int e = 0; e < DV; ++e) {
+            const int idx = tid + e * THREADS;
+            const int pix = idx / (COP / 4), c4 = idx % (COP / 4);
+            const long m = p0 + pix;
+            rd[e] = m < g.M ? *reinterpret_cast<const float4*>(dy + m * g.OC + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto store = [&](int buf) {
+#pragma unroll
+        for (int e = 0; e < XV; ++e) {
+            const int idx = tid + e * THREADS;
+            *reinterpret_cast<float4*>(&Xs[buf * PIX * LDA + (idx / (CIP / 4)) * LDA + 4 * (idx % (CIP / 4))]) = rx[e];
+        }
+#pragma unroll
+        for (int e = 0; e < DV; ++e) {
+            const int idx = tid + e * THREADS;
+            *reinterpret_cast<float4*>(&Ds[buf * PIX * LDB + (idx / (COP / 4)) * LDB + 4 * (idx % (COP / 4))]) = rd[e];
+        }
+    };
+    const int row0 = 16 * TM * (wave / WC), col0 = 16 * TN * (wave % WC);
+    if (nst > 0) load(0);
+    for (int st = 0; st < nst; ++st) {
+        const int buf = st & 1;
+        store(buf);
+        __syncthreads();
+        if (st + 1 < nst) load(st + 1);
+#pragma unroll
+        for (int c = 0; c < PIX / 16; ++c)
+            mma::chunk16<TM, TN, true, false>(Xs + buf * PIX * LDA + 16 * c * LDA, LDA, Ds + buf * PIX * LDB + 16 * c * LDB, LDB,
+                                              row0, col0, acc, lane);
+    }
+    const int l16 = lane & 15, q = lane >> 4;
+    float* out = partial + ((long)blockIdx.x * g.KH * g.KW * g.IC + (long)tap * g.IC) * g.OC;
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                out[(row0 + 16 * a + 4 * q + v) * g.OC + col0 + 16 * b + l16] = acc[a][b][v];
+}
+
+template <int CI_T, int CO_T>
+int launch_wgrad_tile(hipStream_t s, const float* x, const float* dy, float* scratch, const ConvGeom& g, int stages, dim3 grid) {
+    constexpr size_t bytes = (size_t)2 * 64 * ((16 * CI_T + 4) + (16 * CO_T + 4)) * sizeof(float);
+    static bool attr_set = false;
+    auto kern = conv_wgrad_tile_kernel<CI_T, CO_T>;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+            return -1;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(THREADS), bytes, s, x, dy, scratch, g, stages);
+    return DSSPK_LAUNCH_RC();
+}
+
 // d-filter, stage 2: dw[e] = sum over chunks of partial[chunk][e].  A workgroup owns 32 consecutive
 // elements (8 sixteen-byte columns) and splits the chunks over 32 row groups; every lane adds its
 // chunks in ascending order and the row groups are combined by a fixed tree.
@@ -329,7 +429,7 @@ bool geom(ConvGeom& g, int N, int H, int W, int Cin, int Cout, int KH, int KW, i
 }
 
 int wgrad_stages(const ConvGeom& g, int grid_y) {
-    long s = g.M * grid_y / (64L * 128L);
+    long s = g.M * grid_y / (64L * 288L);
     if (s < 1) s = 1;
     if (s > 16) s = 16;
     return (int)s;
@@ -416,7 +516,15 @@ extern "C" int dsspk_conv_bwd_weight(void* stream, const float* x, const float* 
     dim3 grid(chunks, gy);
 #define GO(CI, CO, V) hipLaunchKernelGGL((conv_wgrad_kernel<CI, CO, V>), grid, dim3(THREADS), 0, s, x, dy, scratch, g, stages, rows_total)
 #define GO_CO(CI, V) do { if (Cout == 16) GO(CI, 1, V); else if (Cout == 32) GO(CI, 2, V); else GO(CI, 4, V); } while (0)
-    if (vec) {
+    if (vec && (Cin / 16) * (Cout / 16) >= 4 && Cout >= 32 && (Cin == 16 || Cin == 32 || Cin == 64)) {
+        int rc2;
+        if (Cin == 64 && Cout == 64) rc2 = launch_wgrad_tile<4, 4>(s, x, dy, scratch, g, stages, grid);
+        else if (Cin == 32 && Cout == 64) rc2 = launch_wgrad_tile<2, 4>(s, x, dy, scratch, g, stages, grid);
+        else if (Cin == 32 && Cout == 32) rc2 = launch_wgrad_tile<2, 2>(s, x, dy, scratch, g, stages, grid);
+        else if (Cin == 64 && Cout == 32) rc2 = launch_wgrad_tile<4, 2>(s, x, dy, scratch, g, stages, grid);
+        else rc2 = launch_wgrad_tile<1, 4>(s, x, dy, scratch, g, stages, grid);
+        if (rc2) return rc2;
+    } else if (vec) {
         if (Cin == 16) GO_CO(1, true); else if (Cin == 32) GO_CO(2, true); else if (Cin == 64) GO_CO(4, true); else return -1;
     } else {
         const int tiles = ceil_div(rows_total, 16);

@@ -186,17 +186,28 @@ __device__ __forceinline__ void bn_merge_stats(const float* __restrict__ partial
     const BnLayout L = bn_layout(M, C);
     const int SUB = THREADS / C;
     const int c = threadIdx.x % C, sub = threadIdx.x / C;
+    // all slab results of this lane are fetched in one batch (G <= 128, SUB >= 4: at most 32 per lane)
+    float2 pv[32];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+        const int g = sub + u * SUB;
+        pv[u] = g < L.G ? *reinterpret_cast<const float2*>(partial + ((long)g * C + c) * 2) : make_float2(0.f, 0.f);
+    }
     float s = 0.f;
-    for (int g = sub; g < L.G; g += SUB) {
-        const float n = (float)(min(M, (long)(g + 1) * L.rows_per_block) - (long)g * L.rows_per_block);
-        s = fmaf(n, partial[((long)g * C + c) * 2], s);
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+        const int g = sub + u * SUB;
+        const float n = g < L.G ? (float)(min(M, (long)(g + 1) * L.rows_per_block) - (long)g * L.rows_per_block) : 0.f;
+        s = fmaf(n, pv[u].x, s);
     }
     const float mean = reduce_sub(s, red, c, sub, SUB, C) / (float)M;
     float m2 = 0.f;
-    for (int g = sub; g < L.G; g += SUB) {
-        const float n = (float)(min(M, (long)(g + 1) * L.rows_per_block) - (long)g * L.rows_per_block);
-        const float d = partial[((long)g * C + c) * 2] - mean;
-        m2 += partial[((long)g * C + c) * 2 + 1] + n * d * d;
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+        const int g = sub + u * SUB;
+        const float n = g < L.G ? (float)(min(M, (long)(g + 1) * L.rows_per_block) - (long)g * L.rows_per_block) : 0.f;
+        const float d = pv[u].x - mean;
+        m2 += pv[u].y + n * d * d;
     }
     m2 = reduce_sub(m2, red, c, sub, SUB, C);
     if (sub == 0) {
@@ -263,11 +274,11 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_partial_kernel(const float* __
     const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
     const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
     float4 sb = make_float4(0.f, 0.f, 0.f, 0.f), sg = sb;
-    for (long r0u = r0 + rl; r0u < r1; r0u += 2 * L.RL) {
-        float4 d[2], v[2], o[2];
-        bool ok[2];
+    for (long r0u = r0 + rl; r0u < r1; r0u += 4 * L.RL) {
+        float4 d[4], v[4], o[4];
+        bool ok[4];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {           // two rows in flight per lane
+        for (int u = 0; u < 4; ++u) {           // four rows in flight per lane
             const long r = r0u + u * L.RL;
             ok[u] = r < r1;
             d[u] = ok[u] ? *reinterpret_cast<const float4*>(da + r * C + 4 * vc) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -275,7 +286,7 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_partial_kernel(const float* __
             o[u] = (ok[u] && out) ? *reinterpret_cast<const float4*>(out + r * C + 4 * vc) : make_float4(1.f, 1.f, 1.f, 1.f);
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < 4; ++u) {
             const long r = r0u + u * L.RL;
             if (out) {
                 d[u].x = o[u].x > 0.f ? d[u].x : 0.f; d[u].y = o[u].y > 0.f ? d[u].y : 0.f;
@@ -309,11 +320,15 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restr
         const BnLayout L = bn_layout(M, C);
         const int SUB = THREADS / C;
         const int c = threadIdx.x % C, sub = threadIdx.x / C;
-        float sb = 0.f, sg = 0.f;
-        for (int g = sub; g < L.G; g += SUB) {
-            sb += partial[((long)g * C + c) * 2];
-            sg += partial[((long)g * C + c) * 2 + 1];
+        float2 pv[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {          // one batch of loads (G <= 128, SUB >= 4)
+            const int g = sub + u * SUB;
+            pv[u] = g < L.G ? *reinterpret_cast<const float2*>(partial + ((long)g * C + c) * 2) : make_float2(0.f, 0.f);
         }
+        float sb = 0.f, sg = 0.f;
+#pragma unroll
+        for (int u = 0; u < 32; ++u) { sb += pv[u].x; sg += pv[u].y; }
         sb = reduce_sub(sb, red, c, sub, SUB, C);
         sg = reduce_sub(sg, red, c, sub, SUB, C);
         if (sub == 0) {
@@ -410,7 +425,7 @@ __global__ void softmax_xent_kernel(const float* __restrict__ z, const int32_t* 
 
 inline int grid_for(long items) { return stream_grid(ceil_div(items, THREADS)); }
 inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
-inline bool bn_ok(long M, int C) { return M >= 1 && C >= 4 && C % 4 == 0 && C <= THREADS && THREADS % C == 0; }
+inline bool bn_ok(long M, int C) { return M >= 1 && C >= 4 && C % 4 == 0 && C <= 64 && THREADS % C == 0; }
 
 }  // namespace
 
