@@ -98,7 +98,11 @@ int dssp_pull(dssp_ctx* ctx, int worker, float* dst_dev, uint64_t* version_out);
 /* Alg. 1, worker step 4: g = (1/m) sum_i d loss((x_i, y_i), w_local) / dw, loss = softmax
  * cross-entropy of the network selected by dssp_set_model.  Enqueued on the worker's stream.
  *   x_dev [m][32][32][3], y_dev [m], w_local_dev / grad_dev n_params floats (grad is overwritten),
- *   loss_dev  1 float, mean loss of the mini-batch (may be NULL). */
+ *   loss_dev  1 float, mean loss of the mini-batch (may be NULL).
+ * The launch sequence depends only on (worker, the five pointers): its second use with the same
+ * pointers is captured into a HIP graph and replayed from then on, so callers should cycle through a
+ * fixed set of buffers.  Setting the environment variable DSSP_NO_GRAPH=1 before dssp_create keeps
+ * every step as individual launches. */
 int dssp_worker_step(dssp_ctx* ctx, int worker, const float* x_dev, const int32_t* y_dev,
                      const float* w_local_dev, float* grad_dev, float* loss_dev);
 

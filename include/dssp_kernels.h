@@ -35,8 +35,9 @@ int dsspk_colsum(void* stream, const float* X_dev, float* out_dev, long M, int N
  * Ho = (H + 2*pad - KH)/stride + 1.  bias_dev may be NULL; relu applies max(.,0) to the output. */
 int dsspk_conv_fwd(void* stream, const float* x_dev, const float* w_dev, const float* bias_dev, float* y_dev,
                    int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad, int relu);
-/* dx = transpose of the above applied to dy (gradient w.r.t. the input). */
-int dsspk_conv_bwd_data(void* stream, const float* dy_dev, const float* w_dev, float* dx_dev,
+/* dx = transpose of the above applied to dy (gradient w.r.t. the input), plus add_dev element-wise if it
+ * is not NULL (the gradient arriving through a residual shortcut; add_dev has dx's shape, may not alias dx). */
+int dsspk_conv_bwd_data(void* stream, const float* dy_dev, const float* w_dev, const float* add_dev, float* dx_dev,
                         int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad);
 /* dw[kh][kw][ci][co] = sum over batch and output pixels of x * dy.  Two stages (partial sums per
  * pixel chunk, then a fixed-order reduction).  scratch_dev: dsspk_conv_wgrad_scratch_floats(...) floats. */

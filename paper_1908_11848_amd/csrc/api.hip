@@ -4,6 +4,8 @@
 
 #include <algorithm>
 #include <array>
+#include <map>
+#include <tuple>
 #include <cstdio>
 #include <cstdlib>
 #include <string>
@@ -41,6 +43,14 @@ struct dssp_ctx {
 
     int model_id = DSSP_MODEL_NONE;
     dssp_model::Plan* plan = nullptr;
+
+    // A worker step is a fixed chain of several hundred kernels whose arguments depend only on the
+    // five buffers it is called with.  The first call with a set of buffers runs eagerly, the second
+    // is captured into a HIP graph, later ones replay the graph (one submission instead of hundreds).
+    struct StepGraph { int calls = 0; hipGraph_t graph = nullptr; hipGraphExec_t exec = nullptr; };
+    typedef std::tuple<int, const void*, const void*, const void*, const void*, const void*> StepKey;
+    std::map<StepKey, StepGraph> step_graphs;
+    bool use_graphs = true;
 
     std::string err;
 };
@@ -93,6 +103,14 @@ int synchronization_controller(const dssp_ctx* c, int p) {
     return r_star;
 }
 
+void drop_step_graphs(dssp_ctx* c) {
+    for (auto& kv : c->step_graphs) {
+        if (kv.second.exec) (void)hipGraphExecDestroy(kv.second.exec);
+        if (kv.second.graph) (void)hipGraphDestroy(kv.second.graph);
+    }
+    c->step_graphs.clear();
+}
+
 int check_worker(dssp_ctx* c, int worker) {
     if (!c) return DSSP_EINVAL;
     if (worker < 0 || worker >= c->K) return fail(c, DSSP_EINVAL, "worker index out of range");
@@ -111,6 +129,7 @@ extern "C" int dssp_create(dssp_ctx** out, float* params_dev, int64_t n_params, 
     c->scale = lr / (float)K;
     c->host_only = params_dev == nullptr;
     c->params = params_dev; c->n_params = n_params;
+    if (const char* e = std::getenv("DSSP_NO_GRAPH")) c->use_graphs = !(e[0] && e[0] != '0');
     c->t.assign(K, 0); c->r.assign(K, 0); c->A.assign(K, {0, 0});
     c->blocked.assign(K, 0); c->has_ok.assign(K, 1);
     c->wstream.assign(K, nullptr); c->own_wstream.assign(K, 0);
@@ -160,7 +179,11 @@ extern "C" int dssp_set_stream(dssp_ctx* c, int worker, void* hip_stream) {
 extern "C" int dssp_set_model(dssp_ctx* c, int model_id, int batch, int n_classes, void* workspace_dev, size_t workspace_bytes) {
     if (!c) return DSSP_EINVAL;
     if (c->host_only) return fail(c, DSSP_ESTATE, "host-only context has no model");
-    if (c->plan) { dssp_model::destroy(c->plan); c->plan = nullptr; c->model_id = DSSP_MODEL_NONE; }
+    if (c->plan) {
+        if (int rc = dssp_synchronize(c)) return rc;
+        drop_step_graphs(c);
+        dssp_model::destroy(c->plan); c->plan = nullptr; c->model_id = DSSP_MODEL_NONE;
+    }
     if (model_id == DSSP_MODEL_NONE) return DSSP_OK;
     const int64_t np = dssp_model_param_count(model_id, n_classes);
     if (np < 0 || batch < 1 || n_classes < 2) return fail(c, DSSP_EINVAL, "unknown model, batch < 1 or n_classes < 2");
@@ -199,8 +222,32 @@ extern "C" int dssp_worker_step(dssp_ctx* c, int worker, const float* x_dev, con
     if (!x_dev || !y_dev || !w_local_dev || !grad_dev) return fail(c, DSSP_EINVAL, "null device pointer");
     if (int rc = ensure_stream(c, worker)) return rc;
     std::string err;
-    if (int rc = dssp_model::step(c->plan, worker, c->wstream[worker], x_dev, y_dev, w_local_dev, grad_dev, loss_dev, err))
-        return fail(c, DSSP_EHIP, "worker_step: " + err + " (rc " + std::to_string(rc) + ")");
+    hipStream_t s = c->wstream[worker];
+    dssp_ctx::StepGraph* sg = nullptr;
+    if (c->use_graphs) {
+        sg = &c->step_graphs[dssp_ctx::StepKey(worker, x_dev, y_dev, w_local_dev, grad_dev, loss_dev)];
+        if (sg->exec) {
+            HIP_TRY(c, hipGraphLaunch(sg->exec, s));
+            return DSSP_OK;
+        }
+    }
+    const bool capture = sg && sg->calls >= 1;
+    if (capture) HIP_TRY(c, hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed));
+    const int rc = dssp_model::step(c->plan, worker, s, x_dev, y_dev, w_local_dev, grad_dev, loss_dev, err);
+    if (capture) {
+        hipGraph_t graph = nullptr;
+        const hipError_t e = hipStreamEndCapture(s, &graph);
+        if (rc || e != hipSuccess) {
+            if (graph) (void)hipGraphDestroy(graph);
+            return fail(c, DSSP_EHIP, "worker_step (capture): " + err + " rc " + std::to_string(rc) + " " + hipGetErrorString(e));
+        }
+        sg->graph = graph;
+        HIP_TRY(c, hipGraphInstantiate(&sg->exec, graph, nullptr, nullptr, 0));
+        HIP_TRY(c, hipGraphLaunch(sg->exec, s));
+        return DSSP_OK;
+    }
+    if (rc) return fail(c, DSSP_EHIP, "worker_step: " + err + " (rc " + std::to_string(rc) + ")");
+    if (sg) sg->calls += 1;
     return DSSP_OK;
 }
 
@@ -306,6 +353,7 @@ extern "C" int dssp_destroy(dssp_ctx* c) {
         if (c->server_stream) (void)hipStreamSynchronize(c->server_stream);
         for (int p = 0; p < c->K; ++p)
             if (c->wstream[p]) (void)hipStreamSynchronize(c->wstream[p]);
+        drop_step_graphs(c);
         if (c->plan) dssp_model::destroy(c->plan);
         if (c->ev_apply) (void)hipEventDestroy(c->ev_apply);
         for (int p = 0; p < c->K; ++p) {

@@ -14,7 +14,7 @@
 #include "../../include/dssp_kernels.h"
 
 // Specialised 3x3 / stride 1 / Cin = Cout kernels (k_conv3x3.hip); -2 = shape not covered.
-int conv3x3_direct(hipStream_t s, const float* src, const float* w, float* dst, int N, int HW, int C, bool transposed);
+int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, int N, int HW, int C, bool transposed);
 int wgrad3x3_direct_parts(int N, int HW, int C);
 int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C);
 
@@ -58,8 +58,8 @@ __device__ __forceinline__ bool src_pixel(const ConvGeom& g, int oh, int ow, int
 //          otherwise the reduction index (tap, ci) is flattened and loaded element-wise.
 template <int BM, int BN, bool DGRAD, bool VEC>
 __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
-                                                             const float* __restrict__ bias, float* __restrict__ dst,
-                                                             ConvGeom g, int relu) {
+                                                             const float* __restrict__ bias, const float* __restrict__ add,
+                                                             float* __restrict__ dst, ConvGeom g, int relu) {
     constexpr int WM = BM / 64, WN = BN / 16;
     constexpr int LDB = DGRAD ? mma::LDK : BN + 4;
     constexpr int BS = DGRAD ? BN * mma::LDK : mma::KC * (BN + 4);
@@ -186,6 +186,7 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
                 const long m = m0 + wave * (BM / 4) + 16 * wm + 4 * q + v;
                 if (m >= g.M) continue;
                 float x = acc[wm][wn][v] + bv;
+                if (add) x += add[m * g.OC + col];
                 if (relu) x = fmaxf(x, 0.f);
                 dst[m * g.OC + col] = x;
             }
@@ -436,14 +437,14 @@ int wgrad_stages(const ConvGeom& g, int grid_y) {
 }
 
 template <bool DGRAD, bool VEC>
-int launch_igemm(hipStream_t s, const float* src, const float* w, const float* bias, float* dst, const ConvGeom& g, int relu) {
+int launch_igemm(hipStream_t s, const float* src, const float* w, const float* bias, const float* add, float* dst, const ConvGeom& g, int relu) {
     const int bn = g.OC >= 64 ? 64 : g.OC;
     if (bn != 16 && bn != 32 && bn != 64) return -1;
     if (g.OC % bn) return -1;
     // small problems take 64-pixel tiles so that the grid still covers the chip
     const bool small = g.M < 128L * 512;
     dim3 grid(ceil_div(g.M, small ? 64 : 128), g.OC / bn);
-#define GO(BM, BN) hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, DGRAD, VEC>), grid, dim3(THREADS), 0, s, src, w, bias, dst, g, relu)
+#define GO(BM, BN) hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, DGRAD, VEC>), grid, dim3(THREADS), 0, s, src, w, bias, add, dst, g, relu)
     if (small) { if (bn == 16) GO(64, 16); else if (bn == 32) GO(64, 32); else GO(64, 64); }
     else       { if (bn == 16) GO(128, 16); else if (bn == 32) GO(128, 32); else GO(128, 64); }
 #undef GO
@@ -457,26 +458,26 @@ extern "C" int dsspk_conv_fwd(void* stream, const float* x, const float* w, cons
     ConvGeom g;
     if (!x || !w || !y || !geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W && !bias && !relu) {
-        const int rc = conv3x3_direct((hipStream_t)stream, x, w, y, N, H, Cin, false);
+        const int rc = conv3x3_direct((hipStream_t)stream, x, w, nullptr, y, N, H, Cin, false);
         if (rc != -2) return rc;
     }
-    if (Cin % 16 == 0) return launch_igemm<false, true>((hipStream_t)stream, x, w, bias, y, g, relu);
-    return launch_igemm<false, false>((hipStream_t)stream, x, w, bias, y, g, relu);
+    if (Cin % 16 == 0) return launch_igemm<false, true>((hipStream_t)stream, x, w, bias, nullptr, y, g, relu);
+    return launch_igemm<false, false>((hipStream_t)stream, x, w, bias, nullptr, y, g, relu);
 }
 
-extern "C" int dsspk_conv_bwd_data(void* stream, const float* dy, const float* w, float* dx,
+extern "C" int dsspk_conv_bwd_data(void* stream, const float* dy, const float* w, const float* add, float* dx,
                                    int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
     ConvGeom f;
     if (!dy || !w || !dx || !geom(f, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
     if (Cout % 16) return -1;
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
-        const int rc = conv3x3_direct((hipStream_t)stream, dy, w, dx, N, H, Cin, true);
+        const int rc = conv3x3_direct((hipStream_t)stream, dy, w, add, dx, N, H, Cin, true);
         if (rc != -2) return rc;
     }
     ConvGeom g = f;                       // rows: input pixels; gathered tensor: dy
     g.OH = H; g.OW = W; g.SH = f.OH; g.SW = f.OW; g.IC = Cout; g.OC = Cin;
     g.M = (long)N * H * W;
-    return launch_igemm<true, true>((hipStream_t)stream, dy, w, nullptr, dx, g, 0);
+    return launch_igemm<true, true>((hipStream_t)stream, dy, w, nullptr, add, dx, g, 0);
 }
 
 extern "C" size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {

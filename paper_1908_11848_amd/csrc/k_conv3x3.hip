@@ -35,7 +35,7 @@ struct Cfg {
 
 template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED>
 __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
-                                                          float* __restrict__ dst) {
+                                                          const float* __restrict__ add, float* __restrict__ dst) {
     using K = Cfg<C, HW, R, NSPLIT>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float* Xs = lds;
@@ -123,15 +123,15 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
         for (int v = 0; v < 4; ++v) {
             const int p = run * 16 + 4 * q + v;
             const int h = r_base + p / HW, w = p % HW;
-            float* o = dst + (((long)n * HW + h) * HW + w) * C + co_base + l16;
+            const long off = (((long)n * HW + h) * HW + w) * C + co_base + l16;
 #pragma unroll
-            for (int wn = 0; wn < K::WN; ++wn) o[16 * wn] = acc[wm][wn][v];
+            for (int wn = 0; wn < K::WN; ++wn) dst[off + 16 * wn] = acc[wm][wn][v] + (add ? add[off + 16 * wn] : 0.f);
         }
     }
 }
 
 template <int C, int HW, int R, int NSPLIT, bool T>
-int launch(hipStream_t s, const float* src, const float* w, float* dst, int N) {
+int launch(hipStream_t s, const float* src, const float* w, const float* add, float* dst, int N) {
     using K = Cfg<C, HW, R, NSPLIT>;
     static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
     auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T>;
@@ -141,17 +141,18 @@ int launch(hipStream_t s, const float* src, const float* w, float* dst, int N) {
             return -1;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, dst);
+    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst);
     return DSSPK_LAUNCH_RC();
 }
 
 }  // namespace
 
-// Returns -2 if the shape is not one of the specialised ones (the caller then uses the generic kernel).
-int conv3x3_direct(hipStream_t s, const float* src, const float* w, float* dst, int N, int HW, int C, bool transposed) {
-    if (C == 16 && HW == 32) return transposed ? launch<16, 32, 8, 1, true>(s, src, w, dst, N) : launch<16, 32, 8, 1, false>(s, src, w, dst, N);
-    if (C == 32 && HW == 16) return transposed ? launch<32, 16, 8, 1, true>(s, src, w, dst, N) : launch<32, 16, 8, 1, false>(s, src, w, dst, N);
-    if (C == 64 && HW == 8) return transposed ? launch<64, 8, 8, 2, true>(s, src, w, dst, N) : launch<64, 8, 8, 2, false>(s, src, w, dst, N);
+// dst = conv(src) (+ add, element-wise, if add != NULL).  Returns -2 if the shape is not one of the
+// specialised ones (the caller then uses the generic kernel).
+int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, int N, int HW, int C, bool transposed) {
+    if (C == 16 && HW == 32) return transposed ? launch<16, 32, 8, 1, true>(s, src, w, add, dst, N) : launch<16, 32, 8, 1, false>(s, src, w, add, dst, N);
+    if (C == 32 && HW == 16) return transposed ? launch<32, 16, 8, 1, true>(s, src, w, add, dst, N) : launch<32, 16, 8, 1, false>(s, src, w, add, dst, N);
+    if (C == 64 && HW == 8) return transposed ? launch<64, 8, 8, 2, true>(s, src, w, add, dst, N) : launch<64, 8, 8, 2, false>(s, src, w, add, dst, N);
     return -2;
 }
 

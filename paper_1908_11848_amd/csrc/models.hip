@@ -208,7 +208,7 @@ int step_alexnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, c
     RUN(dsspk_relu_bwd(s, da2, a2, (long)m * 15 * 15 * 64));
     RUN(dsspk_conv_bwd_weight(s, p1, da2, g + cw2, scr, m, 15, 15, 64, 64, 5, 5, 1, 2));
     RUN(dsspk_colsum(s, da2, g + cb2, (long)m * 15 * 15, 64));
-    RUN(dsspk_conv_bwd_data(s, da2, w + cw2, dp1, m, 15, 15, 64, 64, 5, 5, 1, 2));
+    RUN(dsspk_conv_bwd_data(s, da2, w + cw2, nullptr, dp1, m, 15, 15, 64, 64, 5, 5, 1, 2));
     RUN(dsspk_maxpool_bwd(s, dp1, arg1, da1, m, 32, 32, 64));
     RUN(dsspk_relu_bwd(s, da1, a1, (long)m * 32 * 32 * 64));
     RUN(dsspk_conv_bwd_weight(s, x, da1, g + cw1, scr, m, 32, 32, 3, 64, 5, 5, 1, 2));
@@ -253,13 +253,14 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
         // g0 <- dz2 = g0 * [out > 0];  g1 <- d conv2 output
         RUN(dsspk_bn_bwd(s, F(B.c2), w + B.g2, F(B.st2), g0, F(B.out), g1, g + B.g2, g + B.b2, bscr, M, B.cout));
         RUN(dsspk_conv_bwd_weight(s, F(B.a1), g1, g + B.w2, scr, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));
-        RUN(dsspk_conv_bwd_data(s, g1, w + B.w2, g2, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));      // g2 <- d a1
+        RUN(dsspk_conv_bwd_data(s, g1, w + B.w2, nullptr, g2, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));      // g2 <- d a1
         // g2 <- dz1 = g2 * [a1 > 0];  g1 <- d conv1 output
         RUN(dsspk_bn_bwd(s, F(B.c1), w + B.g1, F(B.st1), g2, F(B.a1), g1, g + B.g1, g + B.b1, bscr, M, B.cout));
         RUN(dsspk_conv_bwd_weight(s, xin, g1, g + B.w1, scr, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1));
-        RUN(dsspk_conv_bwd_data(s, g1, w + B.w1, g2, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1)); // g2 <- d xin (conv path)
-        if (B.stride == 1 && B.cin == B.cout) RUN(dsspk_add(s, g2, g0, M * B.cout));
-        else RUN(dsspk_shortcut_bwd_acc(s, g0, g2, m, Ho, Ho, B.cout));
+        // g2 <- d xin: the conv path plus, for an identity shortcut, dz2 (added in the kernel's epilogue)
+        const bool identity = B.stride == 1 && B.cin == B.cout;
+        RUN(dsspk_conv_bwd_data(s, g1, w + B.w1, identity ? g0 : nullptr, g2, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1));
+        if (!identity) RUN(dsspk_shortcut_bwd_acc(s, g0, g2, m, Ho, Ho, B.cout));
         float* t = g0; g0 = g2; g2 = t;
     }
     RUN(dsspk_bn_bwd(s, F(P->stem_c), w + P->stem_g, F(P->stem_st), g0, F(P->stem_a), g1, g + P->stem_g, g + P->stem_b,

@@ -40,7 +40,7 @@ def _conv_case(N, H, Cin, Cout, k, s, p, which, dev):
     if which == "fwd":
         fn = lambda st: L.dsspk_conv_fwd(st, x.data_ptr(), w.data_ptr(), None, y.data_ptr(), N, H, H, Cin, Cout, k, k, s, p, 0)
     elif which == "dgrad":
-        fn = lambda st: L.dsspk_conv_bwd_data(st, dy.data_ptr(), w.data_ptr(), dx.data_ptr(), N, H, H, Cin, Cout, k, k, s, p)
+        fn = lambda st: L.dsspk_conv_bwd_data(st, dy.data_ptr(), w.data_ptr(), None, dx.data_ptr(), N, H, H, Cin, Cout, k, k, s, p)
     else:
         fn = lambda st: L.dsspk_conv_bwd_weight(st, x.data_ptr(), dy.data_ptr(), dw.data_ptr(), scr.data_ptr(), N, H, H, Cin, Cout, k, k, s, p)
     keep = (x, w, y, dy, dx, dw, scr)

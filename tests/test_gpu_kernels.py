@@ -118,8 +118,10 @@ def test_conv_forward_dgrad_wgrad(oracle_nn, case):
     assert rel_l2(host(dw), dwo) < TOL
     if Cin % 16 == 0:
         dx = empty((N, H, H, Cin))
-        rc(L.dsspk_conv_bwd_data(st, DY.data_ptr(), W.data_ptr(), dx.data_ptr(), N, H, H, Cin, Cout, k, k, s, p))
+        rc(L.dsspk_conv_bwd_data(st, DY.data_ptr(), W.data_ptr(), None, dx.data_ptr(), N, H, H, Cin, Cout, k, k, s, p))
         assert rel_l2(host(dx), dxo) < TOL
+        rc(L.dsspk_conv_bwd_data(st, DY.data_ptr(), W.data_ptr(), X.data_ptr(), dx.data_ptr(), N, H, H, Cin, Cout, k, k, s, p))
+        assert rel_l2(host(dx), dxo + x64) < TOL              # with the shortcut's gradient added in the epilogue
 
 
 # ------------------------------------------------------------------ elementwise / pooling
