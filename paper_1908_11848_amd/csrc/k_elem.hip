@@ -186,28 +186,28 @@ __device__ __forceinline__ void bn_merge_stats(const float* __restrict__ partial
     const BnLayout L = bn_layout(M, C);
     const int SUB = THREADS / C;
     const int c = threadIdx.x % C, sub = threadIdx.x / C;
-    // all slab results of this lane are fetched in one batch (G <= 128, SUB >= 4: at most 32 per lane)
+    // All slab results of this lane are fetched in one batch (G <= 128, SUB >= 4: at most 32 per lane).
+    // The loads are unconditional (index clamped) so that they are all in flight together; slabs past
+    // the end get weight 0.
     float2 pv[32];
+    float nn[32];
 #pragma unroll
     for (int u = 0; u < 32; ++u) {
         const int g = sub + u * SUB;
-        pv[u] = g < L.G ? *reinterpret_cast<const float2*>(partial + ((long)g * C + c) * 2) : make_float2(0.f, 0.f);
+        const int gc = min(g, L.G - 1);
+        pv[u] = *reinterpret_cast<const float2*>(partial + ((long)gc * C + c) * 2);
+        const long lo = (long)gc * L.rows_per_block;
+        nn[u] = g < L.G ? (float)(min(M, lo + L.rows_per_block) - lo) : 0.f;
     }
     float s = 0.f;
 #pragma unroll
-    for (int u = 0; u < 32; ++u) {
-        const int g = sub + u * SUB;
-        const float n = g < L.G ? (float)(min(M, (long)(g + 1) * L.rows_per_block) - (long)g * L.rows_per_block) : 0.f;
-        s = fmaf(n, pv[u].x, s);
-    }
+    for (int u = 0; u < 32; ++u) s = fmaf(nn[u], pv[u].x, s);
     const float mean = reduce_sub(s, red, c, sub, SUB, C) / (float)M;
     float m2 = 0.f;
 #pragma unroll
     for (int u = 0; u < 32; ++u) {
-        const int g = sub + u * SUB;
-        const float n = g < L.G ? (float)(min(M, (long)(g + 1) * L.rows_per_block) - (long)g * L.rows_per_block) : 0.f;
         const float d = pv[u].x - mean;
-        m2 += pv[u].y + n * d * d;
+        m2 += nn[u] > 0.f ? pv[u].y + nn[u] * d * d : 0.f;
     }
     m2 = reduce_sub(m2, red, c, sub, SUB, C);
     if (sub == 0) {
@@ -230,34 +230,48 @@ __global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restri
     if (blockIdx.x == 0 && threadIdx.x < 2 * C) stats[threadIdx.x] = sh[threadIdx.x];
     const int VC = C / 4;
     const long total = M * VC;
-    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < total; i += (long)gridDim.x * THREADS) {
-        const int vc = (int)(i % VC);
-        const long row = i / VC;
-        const float4 v = *reinterpret_cast<const float4*>(x + row * C + 4 * vc);
-        const float4 mu = *reinterpret_cast<const float4*>(sh + 4 * vc);
-        const float4 is = *reinterpret_cast<const float4*>(sh + C + 4 * vc);
-        const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
-        const float4 be = *reinterpret_cast<const float4*>(beta + 4 * vc);
-        float4 o;
-        o.x = fmaf((v.x - mu.x) * is.x, ga.x, be.x);
-        o.y = fmaf((v.y - mu.y) * is.y, ga.y, be.y);
-        o.z = fmaf((v.z - mu.z) * is.z, ga.z, be.z);
-        o.w = fmaf((v.w - mu.w) * is.w, ga.w, be.w);
-        if constexpr (SC_MODE == 1) {
-            const float4 s = *reinterpret_cast<const float4*>(sc + row * C + 4 * vc);
-            o.x += s.x; o.y += s.y; o.z += s.z; o.w += s.w;
-        } else if constexpr (SC_MODE == 2) {
-            if (4 * vc < C / 2) {        // first half of the channels: input pixel (2ho, 2wo), C/2 channels wide
-                const int wo = (int)(row % sc_wo);
-                const int ho = (int)((row / sc_wo) % sc_ho);
-                const long n = row / ((long)sc_wo * sc_ho);
-                const float4 s = *reinterpret_cast<const float4*>(
-                    sc + ((n * (2 * sc_ho) + 2 * ho) * (2 * sc_wo) + 2 * wo) * (C / 2) + 4 * vc);
-                o.x += s.x; o.y += s.y; o.z += s.z; o.w += s.w;
+    const long stride = (long)gridDim.x * THREADS;
+    // four independent rows per lane and trip: all loads are issued before the first use
+    for (long i0 = (long)blockIdx.x * THREADS + threadIdx.x; i0 < total; i0 += 4 * stride) {
+        float4 v[4], s4[4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long i = i0 + u * stride;
+            ok[u] = i < total;
+            const int vc = (int)(i % VC);
+            const long row = i / VC;
+            v[u] = ok[u] ? *reinterpret_cast<const float4*>(x + row * C + 4 * vc) : make_float4(0.f, 0.f, 0.f, 0.f);
+            s4[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if constexpr (SC_MODE == 1) {
+                if (ok[u]) s4[u] = *reinterpret_cast<const float4*>(sc + row * C + 4 * vc);
+            } else if constexpr (SC_MODE == 2) {
+                if (ok[u] && 4 * vc < C / 2) {   // first half of the channels: input pixel (2ho, 2wo), C/2 channels wide
+                    const int wo = (int)(row % sc_wo);
+                    const int ho = (int)((row / sc_wo) % sc_ho);
+                    const long n = row / ((long)sc_wo * sc_ho);
+                    s4[u] = *reinterpret_cast<const float4*>(sc + ((n * (2 * sc_ho) + 2 * ho) * (2 * sc_wo) + 2 * wo) * (C / 2) + 4 * vc);
+                }
             }
         }
-        if (relu) { o.x = fmaxf(o.x, 0.f); o.y = fmaxf(o.y, 0.f); o.z = fmaxf(o.z, 0.f); o.w = fmaxf(o.w, 0.f); }
-        *reinterpret_cast<float4*>(y + row * C + 4 * vc) = o;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (!ok[u]) continue;
+            const long i = i0 + u * stride;
+            const int vc = (int)(i % VC);
+            const long row = i / VC;
+            const float4 mu = *reinterpret_cast<const float4*>(sh + 4 * vc);
+            const float4 is = *reinterpret_cast<const float4*>(sh + C + 4 * vc);
+            const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
+            const float4 be = *reinterpret_cast<const float4*>(beta + 4 * vc);
+            float4 o;
+            o.x = fmaf((v[u].x - mu.x) * is.x, ga.x, be.x) + s4[u].x;
+            o.y = fmaf((v[u].y - mu.y) * is.y, ga.y, be.y) + s4[u].y;
+            o.z = fmaf((v[u].z - mu.z) * is.z, ga.z, be.z) + s4[u].z;
+            o.w = fmaf((v[u].w - mu.w) * is.w, ga.w, be.w) + s4[u].w;
+            if (relu) { o.x = fmaxf(o.x, 0.f); o.y = fmaxf(o.y, 0.f); o.z = fmaxf(o.z, 0.f); o.w = fmaxf(o.w, 0.f); }
+            *reinterpret_cast<float4*>(y + row * C + 4 * vc) = o;
+        }
     }
 }
 
@@ -322,13 +336,15 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restr
         const int c = threadIdx.x % C, sub = threadIdx.x / C;
         float2 pv[32];
 #pragma unroll
-        for (int u = 0; u < 32; ++u) {          // one batch of loads (G <= 128, SUB >= 4)
-            const int g = sub + u * SUB;
-            pv[u] = g < L.G ? *reinterpret_cast<const float2*>(partial + ((long)g * C + c) * 2) : make_float2(0.f, 0.f);
-        }
+        for (int u = 0; u < 32; ++u)            // one batch of unconditional loads (G <= 128, SUB >= 4; index clamped)
+            pv[u] = *reinterpret_cast<const float2*>(partial + ((long)min(sub + u * SUB, L.G - 1) * C + c) * 2);
         float sb = 0.f, sg = 0.f;
 #pragma unroll
-        for (int u = 0; u < 32; ++u) { sb += pv[u].x; sg += pv[u].y; }
+        for (int u = 0; u < 32; ++u) {
+            const bool in = sub + u * SUB < L.G;
+            sb += in ? pv[u].x : 0.f;
+            sg += in ? pv[u].y : 0.f;
+        }
         sb = reduce_sub(sb, red, c, sub, SUB, C);
         sg = reduce_sub(sg, red, c, sub, SUB, C);
         if (sub == 0) {
@@ -340,22 +356,37 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restr
     const int VC = C / 4;
     const long total = M * VC;
     const float inv_m = 1.0f / (float)M;
-    for (long i = (long)blockIdx.x * THREADS + threadIdx.x; i < total; i += (long)gridDim.x * THREADS) {
-        const int vc = (int)(i % VC);
-        const long row = i / VC;
-        const float4 v = *reinterpret_cast<const float4*>(x + row * C + 4 * vc);
-        const float4 d = *reinterpret_cast<const float4*>(dz + row * C + 4 * vc);
-        const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
-        const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
-        const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
-        const float4 db = *reinterpret_cast<const float4*>(sh + 4 * vc);
-        const float4 dg = *reinterpret_cast<const float4*>(sh + C + 4 * vc);
-        float4 o;
-        o.x = ga.x * is.x * (d.x - db.x * inv_m - (v.x - mu.x) * is.x * (dg.x * inv_m));
-        o.y = ga.y * is.y * (d.y - db.y * inv_m - (v.y - mu.y) * is.y * (dg.y * inv_m));
-        o.z = ga.z * is.z * (d.z - db.z * inv_m - (v.z - mu.z) * is.z * (dg.z * inv_m));
-        o.w = ga.w * is.w * (d.w - db.w * inv_m - (v.w - mu.w) * is.w * (dg.w * inv_m));
-        *reinterpret_cast<float4*>(dx + row * C + 4 * vc) = o;
+    const long stride = (long)gridDim.x * THREADS;
+    for (long i0 = (long)blockIdx.x * THREADS + threadIdx.x; i0 < total; i0 += 4 * stride) {
+        float4 v[4], d[4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {            // all loads of the trip first
+            const long i = i0 + u * stride;
+            ok[u] = i < total;
+            const int vc = (int)(i % VC);
+            const long row = i / VC;
+            v[u] = ok[u] ? *reinterpret_cast<const float4*>(x + row * C + 4 * vc) : make_float4(0.f, 0.f, 0.f, 0.f);
+            d[u] = ok[u] ? *reinterpret_cast<const float4*>(dz + row * C + 4 * vc) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (!ok[u]) continue;
+            const long i = i0 + u * stride;
+            const int vc = (int)(i % VC);
+            const long row = i / VC;
+            const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
+            const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
+            const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
+            const float4 db = *reinterpret_cast<const float4*>(sh + 4 * vc);
+            const float4 dg = *reinterpret_cast<const float4*>(sh + C + 4 * vc);
+            float4 o;
+            o.x = ga.x * is.x * (d[u].x - db.x * inv_m - (v[u].x - mu.x) * is.x * (dg.x * inv_m));
+            o.y = ga.y * is.y * (d[u].y - db.y * inv_m - (v[u].y - mu.y) * is.y * (dg.y * inv_m));
+            o.z = ga.z * is.z * (d[u].z - db.z * inv_m - (v[u].z - mu.z) * is.z * (dg.z * inv_m));
+            o.w = ga.w * is.w * (d[u].w - db.w * inv_m - (v[u].w - mu.w) * is.w * (dg.w * inv_m));
+            *reinterpret_cast<float4*>(dx + row * C + 4 * vc) = o;
+        }
     }
 }
 
