@@ -88,8 +88,7 @@ def main():
         "weights_finite": finite,
     }
     if not a.no_roofline:
-        out["roofline"] = roofline.measure(a.workload, em)
-        out["roofline_others"] = roofline.measure_others(a.workload, em)
+        out["roofline"], out["roofline_others"] = roofline.measure(a.workload, em)
     em.close()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a.workload, wl)

@@ -71,6 +71,11 @@ int dsspk_bn_fwd(void* stream, const float* x_dev, const float* gamma_dev, const
 int dsspk_bn_bwd(void* stream, const float* x_dev, const float* gamma_dev, const float* stats_dev,
                  float* da_dev, const float* out_dev, float* dx_dev, float* dgamma_dev, float* dbeta_dev,
                  float* scratch_dev, long M, int C);
+/* The two kernels of dsspk_bn_bwd on their own: the per-slab sums (and the ReLU mask written into da), then dx. */
+int dsspk_bn_bwd_reduce(void* stream, const float* x_dev, const float* stats_dev, float* da_dev, const float* out_dev,
+                        float* scratch_dev, long M, int C);
+int dsspk_bn_bwd_dx(void* stream, const float* x_dev, const float* gamma_dev, const float* stats_dev, const float* dz_dev,
+                    float* dx_dev, float* dgamma_dev, float* dbeta_dev, const float* scratch_dev, long M, int C);
 size_t dsspk_bn_scratch_floats(long M, int C);
 
 /* dx[n][2ho][2wo][c] += dy[n][ho][wo][c] for c < C/2 (transpose of shortcut_mode 2). */

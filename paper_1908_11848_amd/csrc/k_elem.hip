@@ -90,7 +90,7 @@ __global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const float* __res
 // ------------------------------------------------------------------ batch normalisation
 // Two kernels per direction, no cross-workgroup synchronisation:
 //   forward : (1) per slab of rows, mean and sum of squared deviations per channel;
-//             (2) every workgroup of the apply kernel merges the (at most 128) slab results in
+//             (2) every workgroup of the apply kernel merges the slab results (at most 32 per lane) in
 //                 its prologue - identical arithmetic in every workgroup - then normalises.
 //   backward: (1) per slab, sum dz and sum dz*xhat (ReLU mask applied, dz written back);
 //             (2) every workgroup of the dx kernel sums the slab results in its prologue.
@@ -104,7 +104,8 @@ __host__ __device__ inline BnLayout bn_layout(long M, int C) {
     BnLayout L;
     L.VC = C / 4;
     L.RL = THREADS / L.VC;
-    long rpb = (M + 127) / 128;                     // at most 128 slabs
+    const long gmax = 32L * (THREADS / C);          // the merge takes at most 32 slab results per lane
+    long rpb = (M + gmax - 1) / gmax;
     if (rpb < 64) rpb = 64;
     rpb = (rpb + L.RL - 1) / L.RL * L.RL;
     L.rows_per_block = rpb;
@@ -134,9 +135,8 @@ __device__ __forceinline__ float4 reduce_rows(float4 v, float4* red, int rl, int
 // Per slab of rows: mean and sum of squared deviations per channel.  Sums are taken about a
 // pivot (the slab's first row) so that no large-minus-large cancellation occurs.
 // partial[(g*C + c)*2 + {0,1}] = {mean_g, M2_g}
-__global__ __launch_bounds__(THREADS) void bn_stats_partial_kernel(const float* __restrict__ x, float* __restrict__ partial, long M, int C) {
+__global__ __launch_bounds__(THREADS) void bn_stats_partial_kernel(const float* __restrict__ x, float* __restrict__ partial, long M, int C, BnLayout L) {
     __shared__ float4 red[THREADS];
-    const BnLayout L = bn_layout(M, C);
     const int rl = threadIdx.x / L.VC, vc = threadIdx.x % L.VC;
     const long r0 = (long)blockIdx.x * L.rows_per_block;
     const long r1 = min(M, r0 + L.rows_per_block);
@@ -182,11 +182,10 @@ __device__ __forceinline__ float reduce_sub(float v, float* red, int c, int sub,
 // Merge of the slab results by the whole workgroup (THREADS / C lanes per channel):
 // mean = sum n_g mean_g / M, M2 = sum (M2_g + n_g (mean_g - mean)^2).
 // On return sh[c] = mean, sh[C + c] = 1 / sqrt(M2 / M + eps) for every channel.
-__device__ __forceinline__ void bn_merge_stats(const float* __restrict__ partial, long M, int C, float eps, float* red, float* sh) {
-    const BnLayout L = bn_layout(M, C);
+__device__ __forceinline__ void bn_merge_stats(const float* __restrict__ partial, long M, int C, float eps, float* red, float* sh, const BnLayout& L) {
     const int SUB = THREADS / C;
     const int c = threadIdx.x % C, sub = threadIdx.x / C;
-    // All slab results of this lane are fetched in one batch (G <= 128, SUB >= 4: at most 32 per lane).
+    // All slab results of this lane are fetched in one batch (G <= 32 * SUB: at most 32 per lane).
     // The loads are unconditional (index clamped) so that they are all in flight together; slabs past
     // the end get weight 0.
     float2 pv[32];
@@ -223,10 +222,11 @@ template <int SC_MODE>
 __global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restrict__ x, const float* __restrict__ gamma,
                                                            const float* __restrict__ beta, const float* __restrict__ partial,
                                                            float* __restrict__ stats, float* __restrict__ y, long M, int C,
-                                                           float eps, int relu, const float* __restrict__ sc, int sc_ho, int sc_wo) {
+                                                           float eps, int relu, const float* __restrict__ sc, int sc_ho, int sc_wo,
+                                                           BnLayout L) {
     __shared__ float red[THREADS];
     __shared__ __attribute__((aligned(16))) float sh[2 * THREADS];
-    bn_merge_stats(partial, M, C, eps, red, sh);
+    bn_merge_stats(partial, M, C, eps, red, sh, L);
     if (blockIdx.x == 0 && threadIdx.x < 2 * C) stats[threadIdx.x] = sh[threadIdx.x];
     const int VC = C / 4;
     const long total = M * VC;
@@ -279,9 +279,8 @@ __global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restri
 // partial[(g*C + c)*2 + {0,1}]
 __global__ __launch_bounds__(THREADS) void bn_bwd_partial_kernel(const float* __restrict__ x, const float* __restrict__ stats,
                                                                  float* __restrict__ da, const float* __restrict__ out,
-                                                                 float* __restrict__ partial, long M, int C) {
+                                                                 float* __restrict__ partial, long M, int C, BnLayout L) {
     __shared__ float4 red[THREADS];
-    const BnLayout L = bn_layout(M, C);
     const int rl = threadIdx.x / L.VC, vc = threadIdx.x % L.VC;
     const long r0 = (long)blockIdx.x * L.rows_per_block;
     const long r1 = min(M, r0 + L.rows_per_block);
@@ -327,16 +326,16 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_partial_kernel(const float* __
 __global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restrict__ x, const float* __restrict__ gamma,
                                                             const float* __restrict__ stats, const float* __restrict__ dz,
                                                             const float* __restrict__ partial, float* __restrict__ dgamma,
-                                                            float* __restrict__ dbeta, float* __restrict__ dx, long M, int C) {
+                                                            float* __restrict__ dbeta, float* __restrict__ dx, long M, int C,
+                                                            BnLayout L) {
     __shared__ float red[THREADS];
     __shared__ __attribute__((aligned(16))) float sh[2 * THREADS];      // [0,C): dbeta, [C,2C): dgamma
     {
-        const BnLayout L = bn_layout(M, C);
         const int SUB = THREADS / C;
         const int c = threadIdx.x % C, sub = threadIdx.x / C;
         float2 pv[32];
 #pragma unroll
-        for (int u = 0; u < 32; ++u)            // one batch of unconditional loads (G <= 128, SUB >= 4; index clamped)
+        for (int u = 0; u < 32; ++u)            // one batch of unconditional loads (G <= 32 * SUB; index clamped)
             pv[u] = *reinterpret_cast<const float2*>(partial + ((long)min(sub + u * SUB, L.G - 1) * C + c) * 2);
         float sb = 0.f, sg = 0.f;
 #pragma unroll
@@ -506,27 +505,45 @@ extern "C" int dsspk_bn_fwd(void* stream, const float* x, const float* gamma, co
     if (shortcut_mode == 2 && ((long)sc_n * sc_ho * sc_wo != M || C % 8)) return -1;
     hipStream_t s = (hipStream_t)stream;
     const BnLayout L = bn_layout(M, C);
-    hipLaunchKernelGGL(bn_stats_partial_kernel, dim3(L.G), dim3(THREADS), 0, s, x, scratch, M, C);
+    hipLaunchKernelGGL(bn_stats_partial_kernel, dim3(L.G), dim3(THREADS), 0, s, x, scratch, M, C, L);
     const int grid = bn_elem_grid(M, C);
     if (shortcut_mode == 0)
-        hipLaunchKernelGGL((bn_apply_kernel<0>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo);
+        hipLaunchKernelGGL((bn_apply_kernel<0>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo, L);
     else if (shortcut_mode == 1)
-        hipLaunchKernelGGL((bn_apply_kernel<1>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo);
+        hipLaunchKernelGGL((bn_apply_kernel<1>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo, L);
     else
-        hipLaunchKernelGGL((bn_apply_kernel<2>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo);
+        hipLaunchKernelGGL((bn_apply_kernel<2>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo, L);
+    return DSSPK_LAUNCH_RC();
+}
+
+static bool bn_bwd_args_ok(const float* x, const float* gamma, const float* stats, const float* da, const float* out,
+                           const float* dx, const float* dgamma, const float* dbeta, const float* scratch, long M, int C) {
+    if (!x || !gamma || !stats || !da || !dx || !dgamma || !dbeta || !scratch || !bn_ok(M, C)) return false;
+    if (!al16(x) || !al16(da) || !al16(dx) || !al16(gamma) || !al16(stats)) return false;
+    return !out || al16(out);
+}
+
+extern "C" int dsspk_bn_bwd_reduce(void* stream, const float* x, const float* stats, float* da, const float* out,
+                                   float* scratch, long M, int C) {
+    if (!bn_bwd_args_ok(x, x, stats, da, out, da, x, x, scratch, M, C)) return -1;
+    const BnLayout L = bn_layout(M, C);
+    hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3(L.G), dim3(THREADS), 0, (hipStream_t)stream, x, stats, da, out, scratch, M, C, L);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_bn_bwd_dx(void* stream, const float* x, const float* gamma, const float* stats, const float* dz,
+                               float* dx, float* dgamma, float* dbeta, const float* scratch, long M, int C) {
+    if (!bn_bwd_args_ok(x, gamma, stats, dz, nullptr, dx, dgamma, dbeta, scratch, M, C)) return -1;
+    hipLaunchKernelGGL(bn_bwd_dx_kernel, dim3(bn_elem_grid(M, C)), dim3(THREADS), 0, (hipStream_t)stream,
+                       x, gamma, stats, dz, scratch, dgamma, dbeta, dx, M, C, bn_layout(M, C));
     return DSSPK_LAUNCH_RC();
 }
 
 extern "C" int dsspk_bn_bwd(void* stream, const float* x, const float* gamma, const float* stats, float* da,
                             const float* out, float* dx, float* dgamma, float* dbeta, float* scratch, long M, int C) {
-    if (!x || !gamma || !stats || !da || !dx || !dgamma || !dbeta || !scratch || !bn_ok(M, C)) return -1;
-    if (!al16(x) || !al16(da) || !al16(dx) || !al16(gamma) || !al16(stats)) return -1;
-    if (out && !al16(out)) return -1;
-    hipStream_t s = (hipStream_t)stream;
-    const BnLayout L = bn_layout(M, C);
-    hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3(L.G), dim3(THREADS), 0, s, x, stats, da, out, scratch, M, C);
-    hipLaunchKernelGGL(bn_bwd_dx_kernel, dim3(bn_elem_grid(M, C)), dim3(THREADS), 0, s, x, gamma, stats, da, scratch, dgamma, dbeta, dx, M, C);
-    return DSSPK_LAUNCH_RC();
+    if (!bn_bwd_args_ok(x, gamma, stats, da, out, dx, dgamma, dbeta, scratch, M, C)) return -1;
+    if (int rc = dsspk_bn_bwd_reduce(stream, x, stats, da, out, scratch, M, C)) return rc;
+    return dsspk_bn_bwd_dx(stream, x, gamma, stats, da, dx, dgamma, dbeta, scratch, M, C);
 }
 
 extern "C" int dsspk_shortcut_bwd_acc(void* stream, const float* dy, float* dx, int N, int Ho, int Wo, int C) {
