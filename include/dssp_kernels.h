@@ -32,9 +32,15 @@ int dsspk_gemm(void* stream, const float* A_dev, long a_rs, long a_cs, const flo
 int dsspk_colsum(void* stream, const float* X_dev, float* out_dev, long M, int N);
 
 /* Convolution (cross-correlation, zero padding), implicit GEMM on fp32 MFMA.
- * Ho = (H + 2*pad - KH)/stride + 1.  bias_dev may be NULL; relu applies max(.,0) to the output. */
+ * Ho = (H + 2*pad - KH)/stride + 1.  bias_dev may be NULL; relu applies max(.,0) to the output.
+ * bn_partial_dev (may be NULL): the kernel also writes, per workgroup tile, the mean and the sum of
+ * squared deviations of every output channel (dsspk_conv_fwd_stat_parts(...) records of
+ * N*Ho*Wo / parts rows each, the layout dsspk_bn_fwd merges when given conv_parts); only for shapes
+ * where dsspk_conv_fwd_stat_parts(...) > 0, without bias / relu. */
 int dsspk_conv_fwd(void* stream, const float* x_dev, const float* w_dev, const float* bias_dev, float* y_dev,
-                   int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad, int relu);
+                   int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad, int relu,
+                   float* bn_partial_dev);
+int dsspk_conv_fwd_stat_parts(int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad);
 /* dx = transpose of the above applied to dy (gradient w.r.t. the input), plus add_dev element-wise if it
  * is not NULL (the gradient arriving through a residual shortcut; add_dev has dx's shape, may not alias dx). */
 int dsspk_conv_bwd_data(void* stream, const float* dy_dev, const float* w_dev, const float* add_dev, float* dx_dev,
@@ -60,10 +66,12 @@ int dsspk_maxpool_bwd(void* stream, const float* dy_dev, const uint8_t* arg_dev,
  * fwd: y = gamma*(x-mean)*invstd + beta (+ shortcut) (ReLU if relu).
  *   shortcut_mode 0: none; 1: sc_dev has y's shape; 2: sc_dev is [N][2Ho][2Wo][C/2], subsampled by
  *   2 in h and w, channels >= C/2 read as zero (Ho, Wo, N given by sc_n, sc_ho, sc_wo).
+ * conv_parts > 0: scratch_dev already holds that many statistics records written by dsspk_conv_fwd
+ *   (the pass over x that computes them is skipped); 0: they are computed here.
  * scratch_dev: dsspk_bn_scratch_floats(M, C) floats (per-slab partial results; one buffer serves one stream at a time). */
 int dsspk_bn_fwd(void* stream, const float* x_dev, const float* gamma_dev, const float* beta_dev, float* y_dev,
                  float* stats_dev, float* scratch_dev, long M, int C, float eps, int relu,
-                 int shortcut_mode, const float* sc_dev, int sc_n, int sc_ho, int sc_wo);
+                 int shortcut_mode, const float* sc_dev, int sc_n, int sc_ho, int sc_wo, int conv_parts);
 /* Backward of ReLU(BN(x) [+ shortcut]) w.r.t. x, gamma, beta.
  *   da_dev    gradient w.r.t. the (post-ReLU) output; overwritten IN PLACE by dz = da * [out > 0]
  *             when out_dev != NULL (out_dev = the saved forward output), left as is otherwise

@@ -60,7 +60,8 @@ _SIGNATURES = {
     "dsspk_gemm": (c_int, [c_void_p, c_void_p, c_long, c_long, c_void_p, c_long, c_long, c_void_p, c_long,
                            c_int, c_int, c_int, c_void_p, c_int]),
     "dsspk_colsum": (c_int, [c_void_p, c_void_p, c_void_p, c_long, c_int]),
-    "dsspk_conv_fwd": (c_int, [c_void_p] * 5 + [c_int] * 10),
+    "dsspk_conv_fwd": (c_int, [c_void_p] * 5 + [c_int] * 10 + [c_void_p]),
+    "dsspk_conv_fwd_stat_parts": (c_int, [c_int] * 9),
     "dsspk_conv_bwd_data": (c_int, [c_void_p] * 5 + [c_int] * 9),
     "dsspk_conv_bwd_weight": (c_int, [c_void_p] * 5 + [c_int] * 9),
     "dsspk_conv_wgrad_scratch_floats": (c_size_t, [c_int] * 9),
@@ -68,7 +69,7 @@ _SIGNATURES = {
     "dsspk_add": (c_int, [c_void_p, c_void_p, c_void_p, c_long]),
     "dsspk_maxpool_fwd": (c_int, [c_void_p] * 4 + [c_int] * 4),
     "dsspk_maxpool_bwd": (c_int, [c_void_p] * 4 + [c_int] * 4),
-    "dsspk_bn_fwd": (c_int, [c_void_p] * 7 + [c_long, c_int, c_float, c_int, c_int, c_void_p, c_int, c_int, c_int]),
+    "dsspk_bn_fwd": (c_int, [c_void_p] * 7 + [c_long, c_int, c_float, c_int, c_int, c_void_p, c_int, c_int, c_int, c_int]),
     "dsspk_bn_bwd": (c_int, [c_void_p] * 10 + [c_long, c_int]),
     "dsspk_bn_bwd_reduce": (c_int, [c_void_p] * 6 + [c_long, c_int]),
     "dsspk_bn_bwd_dx": (c_int, [c_void_p] * 9 + [c_long, c_int]),

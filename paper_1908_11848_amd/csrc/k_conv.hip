@@ -14,7 +14,9 @@
 #include "../../include/dssp_kernels.h"
 
 // Specialised 3x3 / stride 1 / Cin = Cout kernels (k_conv3x3.hip); -2 = shape not covered.
-int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, int N, int HW, int C, bool transposed);
+int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial,
+                   int N, int HW, int C, bool transposed);
+int conv3x3_direct_stat_parts(int N, int HW, int C);
 int wgrad3x3_direct_parts(int N, int HW, int C);
 int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C);
 
@@ -174,6 +176,7 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
         mma::chunk16<WM, WN, false, DGRAD>(As[buf], mma::LDK, Bs[buf], LDB, wave * (BM / 4), 0, acc, lane);
     }
 
+    mma::drain();
     const int l16 = lane & 15, q = lane >> 4;
 #pragma unroll
     for (int wm = 0; wm < WM; ++wm)
@@ -259,6 +262,7 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
         mma::chunk16<CI_T, CO_T, true, false>(Xs + 16 * wave * LDA, LDA, Ds + 16 * wave * LDB, LDB, 0, 0, acc, lane);
     }
 
+    mma::drain();
     // ((w0 + w1) + w2) + w3, element by element
     const int l16 = lane & 15, q = lane >> 4;
     for (int w = 0; w < 4; ++w) {
@@ -360,6 +364,7 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_tile_kernel(const float* _
             mma::chunk16<TM, TN, true, false>(Xs + buf * PIX * LDA + 16 * c * LDA, LDA, Ds + buf * PIX * LDB + 16 * c * LDB, LDB,
                                               row0, col0, acc, lane);
     }
+    mma::drain();
     const int l16 = lane & 15, q = lane >> 4;
     float* out = partial + ((long)blockIdx.x * g.KH * g.KW * g.IC + (long)tap * g.IC) * g.OC;
 #pragma unroll
@@ -453,12 +458,19 @@ int launch_igemm(hipStream_t s, const float* src, const float* w, const float* b
 
 }  // namespace
 
+extern "C" int dsspk_conv_fwd_stat_parts(int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
+    if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) return conv3x3_direct_stat_parts(N, H, Cin);
+    return 0;
+}
+
 extern "C" int dsspk_conv_fwd(void* stream, const float* x, const float* w, const float* bias, float* y,
-                              int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad, int relu) {
+                              int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad, int relu,
+                              float* bn_partial) {
     ConvGeom g;
     if (!x || !w || !y || !geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
+    if (bn_partial && (bias || relu || dsspk_conv_fwd_stat_parts(N, H, W, Cin, Cout, KH, KW, stride, pad) == 0)) return -1;
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W && !bias && !relu) {
-        const int rc = conv3x3_direct((hipStream_t)stream, x, w, nullptr, y, N, H, Cin, false);
+        const int rc = conv3x3_direct((hipStream_t)stream, x, w, nullptr, y, bn_partial, N, H, Cin, false);
         if (rc != -2) return rc;
     }
     if (Cin % 16 == 0) return launch_igemm<false, true>((hipStream_t)stream, x, w, bias, nullptr, y, g, relu);
@@ -471,7 +483,7 @@ extern "C" int dsspk_conv_bwd_data(void* stream, const float* dy, const float* w
     if (!dy || !w || !dx || !geom(f, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
     if (Cout % 16) return -1;
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
-        const int rc = conv3x3_direct((hipStream_t)stream, dy, w, add, dx, N, H, Cin, true);
+        const int rc = conv3x3_direct((hipStream_t)stream, dy, w, add, dx, nullptr, N, H, Cin, true);
         if (rc != -2) return rc;
     }
     ConvGeom g = f;                       // rows: input pixels; gathered tensor: dy

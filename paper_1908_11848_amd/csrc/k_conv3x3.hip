@@ -29,13 +29,15 @@ struct Cfg {
     static constexpr int RUNS = R * HW / 16;       // 16-pixel runs in the band
     static constexpr int WM = RUNS / 4;            // runs per wavefront
     static constexpr int WN = CN / 16;
-    static constexpr size_t LDS_BYTES = (size_t)(XS + WS) * sizeof(float);
+    static constexpr int SS = 4 * CN;              // per-wavefront column sums (batch-norm statistics)
+    static constexpr size_t LDS_BYTES = (size_t)(XS + WS + SS) * sizeof(float);
     static_assert(RUNS % 4 == 0 && WM >= 1, "band must give every wavefront at least one run");
 };
 
 template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED>
 __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
-                                                          const float* __restrict__ add, float* __restrict__ dst) {
+                                                          const float* __restrict__ add, float* __restrict__ dst,
+                                                          float* __restrict__ bn_partial) {
     using K = Cfg<C, HW, R, NSPLIT>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float* Xs = lds;
@@ -115,6 +117,7 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
         }
     }
 
+    mma::drain();
     // ---- store: lane holds rows 4q..4q+3 (pixels of the run) of column l16
 #pragma unroll
     for (int wm = 0; wm < K::WM; ++wm) {
@@ -128,10 +131,46 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
             for (int wn = 0; wn < K::WN; ++wn) dst[off + 16 * wn] = acc[wm][wn][v] + (add ? add[off + 16 * wn] : 0.f);
         }
     }
+
+    // ---- optional: batch-norm statistics of this workgroup's output tile, per channel:
+    //      mean over its R*HW pixels and the sum of squared deviations from that mean
+    //      (bn_partial[(g*C + c)*2 + {0,1}], g = image * bands + band), merged later like row slabs.
+    if (bn_partial) {
+        float* Ss = lds + K::XS + K::WS;
+        constexpr float inv_n = 1.0f / (float)(R * HW);
+        float mean_t[K::WN];
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+            for (int wn = 0; wn < K::WN; ++wn) {
+                float s_ = 0.f;
+#pragma unroll
+                for (int wm = 0; wm < K::WM; ++wm)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float d = pass == 0 ? acc[wm][wn][v] : acc[wm][wn][v] - mean_t[wn];
+                        s_ += pass == 0 ? d : d * d;
+                    }
+                s_ += __shfl_xor(s_, 16);
+                s_ += __shfl_xor(s_, 32);
+                if (q == 0) Ss[wave * K::CN + 16 * wn + l16] = s_;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int wn = 0; wn < K::WN; ++wn) {
+                const int c = 16 * wn + l16;
+                const float tot = (Ss[c] + Ss[K::CN + c]) + (Ss[2 * K::CN + c] + Ss[3 * K::CN + c]);
+                if (pass == 0) mean_t[wn] = tot * inv_n;
+                else if (wave == 0 && q == 0)
+                    *reinterpret_cast<float2*>(bn_partial + ((long)(n * BANDS + band) * C + co_base + c) * 2) = make_float2(mean_t[wn], tot);
+            }
+            __syncthreads();
+        }
+    }
 }
 
 template <int C, int HW, int R, int NSPLIT, bool T>
-int launch(hipStream_t s, const float* src, const float* w, const float* add, float* dst, int N) {
+int launch(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial, int N) {
     using K = Cfg<C, HW, R, NSPLIT>;
     static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
     auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T>;
@@ -141,7 +180,7 @@ int launch(hipStream_t s, const float* src, const float* w, const float* add, fl
             return -1;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst);
+    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst, bn_partial);
     return DSSPK_LAUNCH_RC();
 }
 
@@ -149,11 +188,21 @@ int launch(hipStream_t s, const float* src, const float* w, const float* add, fl
 
 // dst = conv(src) (+ add, element-wise, if add != NULL).  Returns -2 if the shape is not one of the
 // specialised ones (the caller then uses the generic kernel).
-int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, int N, int HW, int C, bool transposed) {
-    if (C == 16 && HW == 32) return transposed ? launch<16, 32, 8, 1, true>(s, src, w, add, dst, N) : launch<16, 32, 8, 1, false>(s, src, w, add, dst, N);
-    if (C == 32 && HW == 16) return transposed ? launch<32, 16, 8, 1, true>(s, src, w, add, dst, N) : launch<32, 16, 8, 1, false>(s, src, w, add, dst, N);
-    if (C == 64 && HW == 8) return transposed ? launch<64, 8, 8, 2, true>(s, src, w, add, dst, N) : launch<64, 8, 8, 2, false>(s, src, w, add, dst, N);
+int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial,
+                   int N, int HW, int C, bool transposed) {
+    if (C == 16 && HW == 32) return transposed ? launch<16, 32, 8, 1, true>(s, src, w, add, dst, bn_partial, N) : launch<16, 32, 8, 1, false>(s, src, w, add, dst, bn_partial, N);
+    if (C == 32 && HW == 16) return transposed ? launch<32, 16, 8, 1, true>(s, src, w, add, dst, bn_partial, N) : launch<32, 16, 8, 1, false>(s, src, w, add, dst, bn_partial, N);
+    if (C == 64 && HW == 8) return transposed ? launch<64, 8, 8, 2, true>(s, src, w, add, dst, bn_partial, N) : launch<64, 8, 8, 2, false>(s, src, w, add, dst, bn_partial, N);
     return -2;
+}
+
+// Number of per-workgroup statistics records (tiles of equal size) the forward kernel emits, 0 if the
+// shape is not covered by it.
+int conv3x3_direct_stat_parts(int N, int HW, int C) {
+    if (C == 16 && HW == 32) return N * 4;
+    if (C == 32 && HW == 16) return N * 2;
+    if (C == 64 && HW == 8) return N;
+    return 0;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -230,6 +279,7 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_kernel(const float* __restri
                 acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Xs[xo[s] + toff], b[s], acc[t], 0, 0, 0);
         }
     }
+    mma::drain();
     float* out = partial + (long)blockIdx.x * 9 * C * C;
     if constexpr (K::SPLIT_K) {
         __syncthreads();                              // tiles no longer needed: reuse LDS for the 4 partial sums

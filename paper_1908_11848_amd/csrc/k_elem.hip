@@ -489,7 +489,7 @@ extern "C" int dsspk_maxpool_bwd(void* stream, const float* dy, const uint8_t* a
 
 extern "C" size_t dsspk_bn_scratch_floats(long M, int C) {
     if (!bn_ok(M, C)) return 0;
-    return (size_t)bn_layout(M, C).G * C * 2;
+    return (size_t)32 * THREADS * 2;          // room for the largest number of records a merge accepts: 32 per lane
 }
 
 // Workgroups of the elementwise BN kernels: each one repeats the merge of the slab results, so keep
@@ -498,14 +498,20 @@ inline int bn_elem_grid(long M, int C) { return stream_grid(ceil_div(M * (C / 4)
 
 extern "C" int dsspk_bn_fwd(void* stream, const float* x, const float* gamma, const float* beta, float* y,
                             float* stats, float* scratch, long M, int C, float eps, int relu,
-                            int shortcut_mode, const float* sc, int sc_n, int sc_ho, int sc_wo) {
+                            int shortcut_mode, const float* sc, int sc_n, int sc_ho, int sc_wo, int conv_parts) {
     if (!x || !gamma || !beta || !y || !stats || !scratch || !bn_ok(M, C)) return -1;
     if (!al16(x) || !al16(y) || !al16(gamma) || !al16(beta) || !al16(stats)) return -1;
     if (shortcut_mode < 0 || shortcut_mode > 2 || (shortcut_mode && (!sc || !al16(sc)))) return -1;
     if (shortcut_mode == 2 && ((long)sc_n * sc_ho * sc_wo != M || C % 8)) return -1;
     hipStream_t s = (hipStream_t)stream;
-    const BnLayout L = bn_layout(M, C);
-    hipLaunchKernelGGL(bn_stats_partial_kernel, dim3(L.G), dim3(THREADS), 0, s, x, scratch, M, C, L);
+    BnLayout L = bn_layout(M, C);
+    if (conv_parts > 0) {           // scratch already holds conv_parts records of M / conv_parts rows each
+        if (M % conv_parts || conv_parts > 32 * (THREADS / C)) return -1;
+        L.G = conv_parts;
+        L.rows_per_block = M / conv_parts;
+    } else {
+        hipLaunchKernelGGL(bn_stats_partial_kernel, dim3(L.G), dim3(THREADS), 0, s, x, scratch, M, C, L);
+    }
     const int grid = bn_elem_grid(M, C);
     if (shortcut_mode == 0)
         hipLaunchKernelGGL((bn_apply_kernel<0>), dim3(grid), dim3(THREADS), 0, s, x, gamma, beta, scratch, stats, y, M, C, eps, relu, sc, sc_ho, sc_wo, L);

@@ -53,6 +53,7 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(const float* __restrict__
         if (kc + 1 < nk) load((kc + 1) * mma::KC);
         mma::chunk16<2, 2, false, true>(As[buf], mma::LDK, Bs[buf], mma::LDK, 32 * (wave >> 1), 32 * (wave & 1), acc, lane);
     }
+    mma::drain();
     const int l16 = lane & 15, q = lane >> 4;
 #pragma unroll
     for (int wm = 0; wm < 2; ++wm)

@@ -58,6 +58,18 @@ __device__ __forceinline__ void chunk16(const float* __restrict__ As, int lda, c
                 acc[wm][wn] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm][s], b[wn][s], acc[wm][wn], 0, 0, 0);
 }
 
+// Call between the last MFMA of a kernel and the first read of its accumulators.  A matrix-core
+// instruction delivers its result several passes after issue and software has to keep dependent
+// reads far enough behind; the compiler does that within straight-line code, but a build of the
+// 3x3 kernel that had a data-dependent branch right after its last MFMA read one accumulator
+// register too early on the short path.  32 idle cycles, fenced against instruction scheduling,
+// cover the longest fp32 MFMA on every path.
+__device__ __forceinline__ void drain() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 template <int WM, int WN>
 __device__ __forceinline__ void zero(floatx4 (&acc)[WM][WN]) {
 #pragma unroll

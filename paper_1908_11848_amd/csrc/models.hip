@@ -184,9 +184,9 @@ int step_alexnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, c
     const int64_t cw1 = 0, cb1 = 4800, cw2 = cb1 + 64, cb2 = cw2 + 102400, fw1 = cb2 + 64, fb1 = fw1 + 3136 * 384,
                   fw2 = fb1 + 384, fb2 = fw2 + 384 * 192, fw3 = fb2 + 192, fb3 = fw3 + 192 * (int64_t)C;
     // forward
-    RUN(dsspk_conv_fwd(s, x, w + cw1, w + cb1, a1, m, 32, 32, 3, 64, 5, 5, 1, 2, 1));
+    RUN(dsspk_conv_fwd(s, x, w + cw1, w + cb1, a1, m, 32, 32, 3, 64, 5, 5, 1, 2, 1, nullptr));
     RUN(dsspk_maxpool_fwd(s, a1, p1, arg1, m, 32, 32, 64));
-    RUN(dsspk_conv_fwd(s, p1, w + cw2, w + cb2, a2, m, 15, 15, 64, 64, 5, 5, 1, 2, 1));
+    RUN(dsspk_conv_fwd(s, p1, w + cw2, w + cb2, a2, m, 15, 15, 64, 64, 5, 5, 1, 2, 1, nullptr));
     RUN(dsspk_maxpool_fwd(s, a2, p2, arg2, m, 15, 15, 64));
     RUN(dsspk_gemm(s, p2, 3136, 1, w + fw1, 384, 1, a3, 384, m, 384, 3136, w + fb1, 1));
     RUN(dsspk_gemm(s, a3, 384, 1, w + fw2, 192, 1, a4, 192, m, 192, 384, w + fb2, 1));
@@ -222,18 +222,21 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
     auto F = [&](size_t off) { return (float*)(ws + off); };
     float *scr = F(P->wg_scratch), *bscr = F(P->bn_scratch);
     // ---- forward
-    RUN(dsspk_conv_fwd(s, x, w + P->stem_w, nullptr, F(P->stem_c), m, 32, 32, 3, 16, 3, 3, 1, 1, 0));
+    RUN(dsspk_conv_fwd(s, x, w + P->stem_w, nullptr, F(P->stem_c), m, 32, 32, 3, 16, 3, 3, 1, 1, 0, nullptr));
     RUN(dsspk_bn_fwd(s, F(P->stem_c), w + P->stem_g, w + P->stem_b, F(P->stem_a), F(P->stem_st), bscr,
-                     (long)m * 1024, 16, eps, 1, 0, nullptr, 0, 0, 0));
+                     (long)m * 1024, 16, eps, 1, 0, nullptr, 0, 0, 0, 0));
     const float* cur = F(P->stem_a);
     for (const ResBlock& B : P->blocks) {
         const int Ho = B.H / B.stride;
         const long M = (long)m * Ho * Ho;
-        RUN(dsspk_conv_fwd(s, cur, w + B.w1, nullptr, F(B.c1), m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1, 0));
-        RUN(dsspk_bn_fwd(s, F(B.c1), w + B.g1, w + B.b1, F(B.a1), F(B.st1), bscr, M, B.cout, eps, 1, 0, nullptr, 0, 0, 0));
-        RUN(dsspk_conv_fwd(s, F(B.a1), w + B.w2, nullptr, F(B.c2), m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1, 0));
+        // where the convolution kernel can, it also emits the per-tile statistics the batch norm needs
+        const int parts1 = dsspk_conv_fwd_stat_parts(m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1);
+        const int parts2 = dsspk_conv_fwd_stat_parts(m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1);
+        RUN(dsspk_conv_fwd(s, cur, w + B.w1, nullptr, F(B.c1), m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1, 0, parts1 ? bscr : nullptr));
+        RUN(dsspk_bn_fwd(s, F(B.c1), w + B.g1, w + B.b1, F(B.a1), F(B.st1), bscr, M, B.cout, eps, 1, 0, nullptr, 0, 0, 0, parts1));
+        RUN(dsspk_conv_fwd(s, F(B.a1), w + B.w2, nullptr, F(B.c2), m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1, 0, parts2 ? bscr : nullptr));
         const int mode = (B.stride == 1 && B.cin == B.cout) ? 1 : 2;
-        RUN(dsspk_bn_fwd(s, F(B.c2), w + B.g2, w + B.b2, F(B.out), F(B.st2), bscr, M, B.cout, eps, 1, mode, cur, m, Ho, Ho));
+        RUN(dsspk_bn_fwd(s, F(B.c2), w + B.g2, w + B.b2, F(B.out), F(B.st2), bscr, M, B.cout, eps, 1, mode, cur, m, Ho, Ho, parts2));
         cur = F(B.out);
     }
     RUN(dsspk_gap_fwd(s, cur, F(P->pooled), m, 64, 64));

@@ -77,7 +77,7 @@ def _conv_case(N, H, Cin, Cout, k, s, p, which, dev):
     scr = torch.empty(max(1, L.dsspk_conv_wgrad_scratch_floats(N, H, H, Cin, Cout, k, k, s, p)), device=dev)
     flops = 2.0 * N * Ho * Ho * Cout * k * k * Cin
     if which == "fwd":
-        fn = lambda st: L.dsspk_conv_fwd(st, x.data_ptr(), w.data_ptr(), None, y.data_ptr(), N, H, H, Cin, Cout, k, k, s, p, 0)
+        fn = lambda st: L.dsspk_conv_fwd(st, x.data_ptr(), w.data_ptr(), None, y.data_ptr(), N, H, H, Cin, Cout, k, k, s, p, 0, None)
     elif which == "dgrad":
         fn = lambda st: L.dsspk_conv_bwd_data(st, dy.data_ptr(), w.data_ptr(), None, dx.data_ptr(), N, H, H, Cin, Cout, k, k, s, p)
     else:
@@ -98,7 +98,7 @@ def _bn_case(H, C, which, dev):
     stats, dg, db = torch.empty(2 * C, device=dev), torch.empty(C, device=dev), torch.empty(C, device=dev)
     scr = torch.empty(L.dsspk_bn_scratch_floats(M, C), device=dev)
     fwd = lambda st: L.dsspk_bn_fwd(st, x.data_ptr(), g.data_ptr(), b.data_ptr(), y.data_ptr(), stats.data_ptr(),
-                                    scr.data_ptr(), M, C, 1e-5, 1, 1, sc.data_ptr(), BATCH, H, H)
+                                    scr.data_ptr(), M, C, 1e-5, 1, 1, sc.data_ptr(), BATCH, H, H, 0)
     bwd = lambda st: L.dsspk_bn_bwd(st, x.data_ptr(), g.data_ptr(), stats.data_ptr(), da.data_ptr(), y.data_ptr(),
                                     dx.data_ptr(), dg.data_ptr(), db.data_ptr(), scr.data_ptr(), M, C)
     red = lambda st: L.dsspk_bn_bwd_reduce(st, x.data_ptr(), stats.data_ptr(), da.data_ptr(), y.data_ptr(), scr.data_ptr(), M, C)

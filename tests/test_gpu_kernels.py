@@ -103,7 +103,7 @@ def test_conv_forward_dgrad_wgrad(oracle_nn, case):
     L = B.lib()
     y = empty((N, Ho, Ho, Cout))
     rc(L.dsspk_conv_fwd(st, X.data_ptr(), W.data_ptr(), Bv.data_ptr() if br else None, y.data_ptr(),
-                        N, H, H, Cin, Cout, k, k, s, p, int(br)))
+                        N, H, H, Cin, Cout, k, k, s, p, int(br), None))
     x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
     yo = oracle_nn.conv2d_fwd(x64, w64, b.astype(np.float64) if br else None, s, p)
     if br:
@@ -122,6 +122,29 @@ def test_conv_forward_dgrad_wgrad(oracle_nn, case):
         assert rel_l2(host(dx), dxo) < TOL
         rc(L.dsspk_conv_bwd_data(st, DY.data_ptr(), W.data_ptr(), X.data_ptr(), dx.data_ptr(), N, H, H, Cin, Cout, k, k, s, p))
         assert rel_l2(host(dx), dxo + x64) < TOL              # with the shortcut's gradient added in the epilogue
+
+
+@pytest.mark.parametrize("N,H,C", [(3, 32, 16), (5, 16, 32), (4, 8, 64), (128, 32, 16), (128, 8, 64)])
+def test_conv_emits_batchnorm_statistics(oracle_nn, N, H, C):
+    """conv -> BN with the statistics taken from the convolution kernel's per-tile records."""
+    g = np.random.default_rng(N + H + C)
+    x, w = f32(g, (N, H, H, C)), f32(g, (3, 3, C, C), (2.0 / (9 * C)) ** 0.5)
+    gamma, beta = (1 + 0.2 * g.standard_normal(C)).astype(np.float32), f32(g, C, 0.3)
+    L = B.lib()
+    st = stream_ptr()
+    parts = L.dsspk_conv_fwd_stat_parts(N, H, H, C, C, 3, 3, 1, 1)
+    assert parts > 0
+    M = N * H * H
+    X, W, Ga, Be = dev(x), dev(w), dev(gamma), dev(beta)
+    y = empty((N, H, H, C)); out = empty((N, H, H, C)); stats = empty(2 * C)
+    scratch = empty(L.dsspk_bn_scratch_floats(M, C))
+    rc(L.dsspk_conv_fwd(st, X.data_ptr(), W.data_ptr(), None, y.data_ptr(), N, H, H, C, C, 3, 3, 1, 1, 0, scratch.data_ptr()))
+    rc(L.dsspk_bn_fwd(st, y.data_ptr(), Ga.data_ptr(), Be.data_ptr(), out.data_ptr(), stats.data_ptr(), scratch.data_ptr(),
+                      M, C, 1e-5, 1, 0, None, 0, 0, 0, parts))
+    yo = oracle_nn.conv2d_fwd(x.astype(np.float64), w.astype(np.float64), None, 1, 1)
+    oo, mean, invstd = oracle_nn.bn_fwd(yo, gamma.astype(np.float64), beta.astype(np.float64))
+    assert rel_l2(host(stats)[:C], mean) < 5e-6 and rel_l2(host(stats)[C:], invstd) < TOL
+    assert rel_l2(host(out), np.maximum(oo, 0)) < 5e-6
 
 
 # ------------------------------------------------------------------ elementwise / pooling
@@ -176,7 +199,7 @@ def test_batchnorm_forward_backward(oracle_nn, N, H, C, mode, relu):
     SC = dev(sc) if sc is not None else None
     y = empty((N, H, H, C)); stats = empty(2 * C); scratch = empty(L.dsspk_bn_scratch_floats(M, C))
     rc(L.dsspk_bn_fwd(st, X.data_ptr(), Ga.data_ptr(), Be.data_ptr(), y.data_ptr(), stats.data_ptr(), scratch.data_ptr(),
-                      M, C, 1e-5, relu, mode, SC.data_ptr() if SC is not None else None, N, H, H))
+                      M, C, 1e-5, relu, mode, SC.data_ptr() if SC is not None else None, N, H, H, 0))
     x64 = x.astype(np.float64)
     yo, mean, invstd = oracle_nn.bn_fwd(x64, gamma.astype(np.float64), beta.astype(np.float64))
     if mode == 1:

@@ -314,6 +314,34 @@ def test_server_stress_config5(oracle_nn):
     em.close()
 
 
+# ------------------------------------------------------------------ graph replay
+def test_graph_replay_is_bit_identical_to_eager(oracle_nn):
+    """A worker step runs eagerly the first time it sees a set of buffers, is captured into a HIP graph
+    the second time and replayed afterwards; every variant must give the same bits, also with other
+    work (pulls, applies, other workers' steps) interleaved between the replays."""
+    K, batch, model = 2, 8, "resnet8"
+    w0 = inputs.init_weights(segs_of(model, 10), 4, jitter=0.1)
+    xs, ys = inputs.batches(4, K, 2, batch, 10)
+    em = Emulation(model, K, 3, 12, 0.05, w0, batch, 10, xs, ys)
+    for p in range(K):
+        B.dssp_pull(em.ctx, p, em.w_local[p])
+    ref = {}
+    for rep in range(5):                       # eager, capture, replay, replay, replay
+        for p in range(K):
+            for j in range(2):
+                em.grad[p].fill_(float("nan"))
+                torch.cuda.synchronize()
+                em.step(p, j)
+                g, loss = em.worker_grad(p)
+                assert np.isfinite(g).all()
+                if rep == 0:
+                    ref[(p, j)] = (g.copy(), loss)
+                else:
+                    assert np.array_equal(g, ref[(p, j)][0]) and loss == ref[(p, j)][1], (rep, p, j)
+        B.dssp_pull(em.ctx, 0, em.w_local[0])  # same weights again (no push happened): bits must not change
+    em.close()
+
+
 # ------------------------------------------------------------------ error paths (host side; nothing faults)
 def test_error_codes():
     import torch
