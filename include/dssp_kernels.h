@@ -41,6 +41,16 @@ int dsspk_conv_fwd(void* stream, const float* x_dev, const float* w_dev, const f
                    int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad, int relu,
                    float* bn_partial_dev);
 int dsspk_conv_fwd_stat_parts(int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad);
+/* 3x3 / stride 1 / pad 1 / C -> C convolution of a = ReLU(BN(src) (+ shortcut)) without a separate batch-norm
+ * pass: the kernel normalises src while loading it.  src is [N][H][H][C]; records_dev holds in_parts statistics
+ * records of src as written by dsspk_conv_fwd(..., bn_partial_dev) for the same shape; shortcut_dev (may be
+ * NULL) has src's shape.  Side outputs: act_out_dev = a, stats_out_dev = mean[C], invstd[C] (what dsspk_bn_fwd
+ * would have produced).  bn_partial_dev (may be NULL): statistics records of y, which must not be the buffer
+ * records_dev points to.  Only shapes with dsspk_conv_fwd_stat_parts(...) > 0; returns -1 otherwise. */
+int dsspk_conv_fwd_prebn(void* stream, const float* src_dev, const float* records_dev, int in_parts,
+                         const float* gamma_dev, const float* beta_dev, float eps, const float* shortcut_dev,
+                         float* act_out_dev, float* stats_out_dev, const float* w_dev, float* y_dev,
+                         float* bn_partial_dev, int N, int H, int C);
 /* dx = transpose of the above applied to dy (gradient w.r.t. the input), plus add_dev element-wise if it
  * is not NULL (the gradient arriving through a residual shortcut; add_dev has dx's shape, may not alias dx). */
 int dsspk_conv_bwd_data(void* stream, const float* dy_dev, const float* w_dev, const float* add_dev, float* dx_dev,

@@ -17,6 +17,9 @@
 int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial,
                    int N, int HW, int C, bool transposed);
 int conv3x3_direct_stat_parts(int N, int HW, int C);
+int conv3x3_direct_prebn(hipStream_t s, const float* src, const float* records, int in_parts, const float* gamma,
+                         const float* beta, float eps, const float* shortcut, float* act_out, float* stats_out,
+                         const float* w, float* dst, float* bn_partial, int N, int HW, int C);
 int wgrad3x3_direct_parts(int N, int HW, int C);
 int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C);
 
@@ -475,6 +478,16 @@ extern "C" int dsspk_conv_fwd(void* stream, const float* x, const float* w, cons
     }
     if (Cin % 16 == 0) return launch_igemm<false, true>((hipStream_t)stream, x, w, bias, nullptr, y, g, relu);
     return launch_igemm<false, false>((hipStream_t)stream, x, w, bias, nullptr, y, g, relu);
+}
+
+extern "C" int dsspk_conv_fwd_prebn(void* stream, const float* src, const float* records, int in_parts, const float* gamma,
+                                    const float* beta, float eps, const float* shortcut, float* act_out, float* stats_out,
+                                    const float* w, float* y, float* bn_partial, int N, int H, int C) {
+    if (!src || !records || !gamma || !beta || !act_out || !stats_out || !w || !y || N < 1) return -1;
+    if (conv3x3_direct_stat_parts(N, H, C) == 0) return -1;
+    const int rc = conv3x3_direct_prebn((hipStream_t)stream, src, records, in_parts, gamma, beta, eps, shortcut, act_out, stats_out,
+                                        w, y, bn_partial, N, H, C);
+    return rc == -2 ? -1 : rc;
 }
 
 extern "C" int dsspk_conv_bwd_data(void* stream, const float* dy, const float* w, const float* add, float* dx,

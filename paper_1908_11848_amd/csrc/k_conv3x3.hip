@@ -13,6 +13,7 @@
 // Gradient w.r.t. the input of such a convolution is the same operation on dy with the filter
 // taps reversed and its two channel indices swapped; only the filter load differs.
 #include "mma.hpp"
+#include "bn_merge.hpp"
 #include "../../include/dssp_kernels.h"
 
 namespace {
@@ -30,14 +31,32 @@ struct Cfg {
     static constexpr int WM = RUNS / 4;            // runs per wavefront
     static constexpr int WN = CN / 16;
     static constexpr int SS = 4 * CN;              // per-wavefront column sums (batch-norm statistics)
-    static constexpr size_t LDS_BYTES = (size_t)(XS + WS + SS) * sizeof(float);
+    static constexpr int PS = THREADS + 2 * C;     // merge of the input's batch-norm records: tree + (mean, invstd)
+    static constexpr size_t LDS_BYTES = (size_t)(XS + WS + SS + PS) * sizeof(float);
     static_assert(RUNS % 4 == 0 && WM >= 1, "band must give every wavefront at least one run");
 };
 
-template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED>
+// Normalisation applied to the input while it is loaded (PRE != 0): the kernel then computes
+//   a = ReLU(gamma * (src - mean) * invstd + beta (+ shortcut))   and   dst = conv(a),
+// i.e. the batch norm + ReLU that separates two convolutions never runs as a pass of its own.
+// mean / invstd come from the statistics records of src (merged by every workgroup in its
+// prologue); the workgroups also write `a` (their own rows) and mean / invstd for the backward pass.
+struct PreBn {
+    const float* records;      // statistics records of src
+    bnm::BnLayout L;           // their layout
+    long M;                    // rows of src (= N * HW * HW)
+    const float* gamma;
+    const float* beta;
+    float eps;
+    const float* shortcut;     // PRE == 2: added before the ReLU, same shape as src
+    float* act_out;            // a
+    float* stats_out;          // mean[C], invstd[C]
+};
+
+template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED, int PRE>
 __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
                                                           const float* __restrict__ add, float* __restrict__ dst,
-                                                          float* __restrict__ bn_partial) {
+                                                          float* __restrict__ bn_partial, PreBn pre) {
     using K = Cfg<C, HW, R, NSPLIT>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float* Xs = lds;
@@ -52,13 +71,37 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
 
     // ---- input halo tile, zero outside the image
     constexpr int V = C / 4;
+    float* Sh = lds + K::XS + K::WS + K::SS + THREADS;       // mean[C], invstd[C] of the input (PRE)
+    if constexpr (PRE != 0) {
+        bnm::bn_merge_stats(pre.records, pre.M, C, pre.eps, lds + K::XS + K::WS + K::SS, Sh, pre.L);
+        if (blockIdx.x == 0 && tid < 2 * C) pre.stats_out[tid] = Sh[tid];
+    }
     for (int idx = tid; idx < (R + 2) * K::TW * V; idx += THREADS) {
         const int v = idx % V;
         const int pc = (idx / V) % K::TW, pr = idx / (V * K::TW);
         const int h = r_base + pr - 1, w = pc - 1;
         float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (h >= 0 && h < HW && w >= 0 && w < HW)
-            val = *reinterpret_cast<const float4*>(src + (((long)n * HW + h) * HW + w) * C + 4 * v);
+        if (h >= 0 && h < HW && w >= 0 && w < HW) {
+            const long off = (((long)n * HW + h) * HW + w) * C + 4 * v;
+            val = *reinterpret_cast<const float4*>(src + off);
+            if constexpr (PRE != 0) {
+                const float4 mu = *reinterpret_cast<const float4*>(Sh + 4 * v);
+                const float4 is = *reinterpret_cast<const float4*>(Sh + C + 4 * v);
+                const float4 ga = *reinterpret_cast<const float4*>(pre.gamma + 4 * v);
+                const float4 be = *reinterpret_cast<const float4*>(pre.beta + 4 * v);
+                val.x = fmaf((val.x - mu.x) * is.x, ga.x, be.x);
+                val.y = fmaf((val.y - mu.y) * is.y, ga.y, be.y);
+                val.z = fmaf((val.z - mu.z) * is.z, ga.z, be.z);
+                val.w = fmaf((val.w - mu.w) * is.w, ga.w, be.w);
+                if constexpr (PRE == 2) {
+                    const float4 sc = *reinterpret_cast<const float4*>(pre.shortcut + off);
+                    val.x += sc.x; val.y += sc.y; val.z += sc.z; val.w += sc.w;
+                }
+                val.x = fmaxf(val.x, 0.f); val.y = fmaxf(val.y, 0.f); val.z = fmaxf(val.z, 0.f); val.w = fmaxf(val.w, 0.f);
+                // the band's own rows (not the halo rows) are this workgroup's part of `a`
+                if (split == 0 && pr >= 1 && pr <= R) *reinterpret_cast<float4*>(pre.act_out + off) = val;
+            }
+        }
         *reinterpret_cast<float4*>(&Xs[(pr * K::TW + pc) * K::LDC + 4 * v]) = val;
     }
     // ---- filter slab Ws[tap][j][k]: j = output channel of this kernel, k = reduction channel.
@@ -169,18 +212,19 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
     }
 }
 
-template <int C, int HW, int R, int NSPLIT, bool T>
-int launch(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial, int N) {
+template <int C, int HW, int R, int NSPLIT, bool T, int PRE = 0>
+int launch(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial, int N,
+           const PreBn& pre = PreBn()) {
     using K = Cfg<C, HW, R, NSPLIT>;
     static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
-    auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T>;
+    auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T, PRE>;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)K::LDS_BYTES) != hipSuccess)
             return -1;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst, bn_partial);
+    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst, bn_partial, pre);
     return DSSPK_LAUNCH_RC();
 }
 
@@ -193,6 +237,32 @@ int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float*
     if (C == 16 && HW == 32) return transposed ? launch<16, 32, 8, 1, true>(s, src, w, add, dst, bn_partial, N) : launch<16, 32, 8, 1, false>(s, src, w, add, dst, bn_partial, N);
     if (C == 32 && HW == 16) return transposed ? launch<32, 16, 8, 1, true>(s, src, w, add, dst, bn_partial, N) : launch<32, 16, 8, 1, false>(s, src, w, add, dst, bn_partial, N);
     if (C == 64 && HW == 8) return transposed ? launch<64, 8, 8, 2, true>(s, src, w, add, dst, bn_partial, N) : launch<64, 8, 8, 2, false>(s, src, w, add, dst, bn_partial, N);
+    return -2;
+}
+
+// Forward convolution of a = ReLU(BN(src) (+ shortcut)), see PreBn.  in_parts: number of equal-sized
+// statistics records of src in `records` (as emitted by the forward kernel for the same shape).
+int conv3x3_direct_prebn(hipStream_t s, const float* src, const float* records, int in_parts, const float* gamma,
+                         const float* beta, float eps, const float* shortcut, float* act_out, float* stats_out,
+                         const float* w, float* dst, float* bn_partial, int N, int HW, int C) {
+    PreBn pre;
+    pre.records = records;
+    pre.M = (long)N * HW * HW;
+    if (in_parts < 1 || pre.M % in_parts || in_parts > 32 * (THREADS / C)) return -1;
+    pre.L = bnm::bn_layout(pre.M, C);
+    pre.L.G = in_parts;
+    pre.L.rows_per_block = pre.M / in_parts;
+    pre.gamma = gamma; pre.beta = beta; pre.eps = eps;
+    pre.shortcut = shortcut; pre.act_out = act_out; pre.stats_out = stats_out;
+    if (C == 16 && HW == 32)
+        return shortcut ? launch<16, 32, 8, 1, false, 2>(s, src, w, nullptr, dst, bn_partial, N, pre)
+                        : launch<16, 32, 8, 1, false, 1>(s, src, w, nullptr, dst, bn_partial, N, pre);
+    if (C == 32 && HW == 16)
+        return shortcut ? launch<32, 16, 8, 1, false, 2>(s, src, w, nullptr, dst, bn_partial, N, pre)
+                        : launch<32, 16, 8, 1, false, 1>(s, src, w, nullptr, dst, bn_partial, N, pre);
+    if (C == 64 && HW == 8)
+        return shortcut ? launch<64, 8, 8, 2, false, 2>(s, src, w, nullptr, dst, bn_partial, N, pre)
+                        : launch<64, 8, 8, 2, false, 1>(s, src, w, nullptr, dst, bn_partial, N, pre);
     return -2;
 }
 

@@ -42,7 +42,7 @@ struct Plan {
     std::vector<Tens> tens;
 
     // common tail
-    size_t logits = 0, dlogits = 0, wg_scratch = 0, bn_scratch = 0;
+    size_t logits = 0, dlogits = 0, wg_scratch = 0, bn_scratch = 0, bn_scratch2 = 0;
     // MLP
     size_t mlp_a1 = 0, mlp_da1 = 0;
     // AlexNet-style
@@ -144,6 +144,7 @@ struct Plan {
         tens.push_back({2, logits, (int64_t)m * classes});
         wg_scratch = a.floats(wg ? wg : 1);
         bn_scratch = a.floats(bn ? bn : 1);
+        bn_scratch2 = a.floats(bn ? bn : 1);
         per_worker = a.off;
         return true;
     }
@@ -225,18 +226,45 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
     RUN(dsspk_conv_fwd(s, x, w + P->stem_w, nullptr, F(P->stem_c), m, 32, 32, 3, 16, 3, 3, 1, 1, 0, nullptr));
     RUN(dsspk_bn_fwd(s, F(P->stem_c), w + P->stem_g, w + P->stem_b, F(P->stem_a), F(P->stem_st), bscr,
                      (long)m * 1024, 16, eps, 1, 0, nullptr, 0, 0, 0, 0));
+    // Statistics records ping-pong between two buffers: conv1 writes recA, conv2 reads recA and writes recB,
+    // the next block's conv1 reads recB.  A "regular" block (stride 1, same width, shape covered by the direct
+    // kernels) has its two batch norms folded into the loaders of the convolutions that consume them:
+    //   conv1 [+ BN2/shortcut/ReLU of the previous block in its loader]  ->  conv2 [+ BN1/ReLU in its loader]
+    // and only the last block of a run materialises its output with the stand-alone BN kernels.
+    float *recA = bscr, *recB = F(P->bn_scratch2);
+    const int nb = (int)P->blocks.size();
+    auto regular = [&](int i) {
+        const ResBlock& b = P->blocks[i];
+        return b.stride == 1 && b.cin == b.cout && dsspk_conv_fwd_stat_parts(m, b.H, b.H, b.cin, b.cout, 3, 3, 1, 1) > 0;
+    };
     const float* cur = F(P->stem_a);
-    for (const ResBlock& B : P->blocks) {
+    bool pending = false;            // the previous block's output is not written yet (its BN2 is folded into this conv1)
+    for (int bi = 0; bi < nb; ++bi) {
+        const ResBlock& B = P->blocks[bi];
         const int Ho = B.H / B.stride;
         const long M = (long)m * Ho * Ho;
-        // where the convolution kernel can, it also emits the per-tile statistics the batch norm needs
         const int parts1 = dsspk_conv_fwd_stat_parts(m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1);
         const int parts2 = dsspk_conv_fwd_stat_parts(m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1);
-        RUN(dsspk_conv_fwd(s, cur, w + B.w1, nullptr, F(B.c1), m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1, 0, parts1 ? bscr : nullptr));
-        RUN(dsspk_bn_fwd(s, F(B.c1), w + B.g1, w + B.b1, F(B.a1), F(B.st1), bscr, M, B.cout, eps, 1, 0, nullptr, 0, 0, 0, parts1));
-        RUN(dsspk_conv_fwd(s, F(B.a1), w + B.w2, nullptr, F(B.c2), m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1, 0, parts2 ? bscr : nullptr));
-        const int mode = (B.stride == 1 && B.cin == B.cout) ? 1 : 2;
-        RUN(dsspk_bn_fwd(s, F(B.c2), w + B.g2, w + B.b2, F(B.out), F(B.st2), bscr, M, B.cout, eps, 1, mode, cur, m, Ho, Ho, parts2));
+        if (pending) {
+            const ResBlock& Pv = P->blocks[bi - 1];
+            const float* pin = bi >= 2 ? F(P->blocks[bi - 2].out) : F(P->stem_a);         // the previous block's input = its shortcut
+            RUN(dsspk_conv_fwd_prebn(s, F(Pv.c2), recB, parts2, w + Pv.g2, w + Pv.b2, eps, pin, F(Pv.out), F(Pv.st2),
+                                     w + B.w1, F(B.c1), recA, m, B.H, B.cin));
+        } else {
+            RUN(dsspk_conv_fwd(s, cur, w + B.w1, nullptr, F(B.c1), m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1, 0, parts1 ? recA : nullptr));
+        }
+        if (parts1 && parts2) {
+            RUN(dsspk_conv_fwd_prebn(s, F(B.c1), recA, parts1, w + B.g1, w + B.b1, eps, nullptr, F(B.a1), F(B.st1),
+                                     w + B.w2, F(B.c2), recB, m, Ho, B.cout));
+        } else {
+            RUN(dsspk_bn_fwd(s, F(B.c1), w + B.g1, w + B.b1, F(B.a1), F(B.st1), recA, M, B.cout, eps, 1, 0, nullptr, 0, 0, 0, parts1));
+            RUN(dsspk_conv_fwd(s, F(B.a1), w + B.w2, nullptr, F(B.c2), m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1, 0, parts2 ? recB : nullptr));
+        }
+        pending = regular(bi) && parts2 > 0 && bi + 1 < nb && regular(bi + 1);
+        if (!pending) {
+            const int mode = (B.stride == 1 && B.cin == B.cout) ? 1 : 2;
+            RUN(dsspk_bn_fwd(s, F(B.c2), w + B.g2, w + B.b2, F(B.out), F(B.st2), recB, M, B.cout, eps, 1, mode, cur, m, Ho, Ho, parts2));
+        }
         cur = F(B.out);
     }
     RUN(dsspk_gap_fwd(s, cur, F(P->pooled), m, 64, 64));

@@ -147,6 +147,42 @@ def test_conv_emits_batchnorm_statistics(oracle_nn, N, H, C):
     assert rel_l2(host(out), np.maximum(oo, 0)) < 5e-6
 
 
+@pytest.mark.parametrize("N,H,C,with_sc", [(3, 32, 16, False), (5, 16, 32, True), (4, 8, 64, True), (128, 32, 16, True), (128, 8, 64, False)])
+def test_conv_with_batchnorm_folded_into_its_loader(oracle_nn, N, H, C, with_sc):
+    """c -> [BN + (shortcut) + ReLU folded into the loader] -> conv, against the three oracle layers;
+    the side outputs (activation, mean / invstd, statistics records of y) are checked too."""
+    g = np.random.default_rng(N * 7 + H + C)
+    x = f32(g, (N, H, H, C))
+    w0, w1 = f32(g, (3, 3, C, C), (2.0 / (9 * C)) ** 0.5), f32(g, (3, 3, C, C), (2.0 / (9 * C)) ** 0.5)
+    gamma, beta = (1 + 0.2 * g.standard_normal(C)).astype(np.float32), f32(g, C, 0.3)
+    sc = f32(g, (N, H, H, C)) if with_sc else None
+    L = B.lib()
+    st = stream_ptr()
+    M = N * H * H
+    parts = L.dsspk_conv_fwd_stat_parts(N, H, H, C, C, 3, 3, 1, 1)
+    X, W0, W1, Ga, Be = dev(x), dev(w0), dev(w1), dev(gamma), dev(beta)
+    SC = dev(sc) if with_sc else None
+    c = empty((N, H, H, C)); a = empty((N, H, H, C)); y = empty((N, H, H, C)); stats = empty(2 * C)
+    recA, recB = empty(L.dsspk_bn_scratch_floats(M, C)), empty(L.dsspk_bn_scratch_floats(M, C))
+    rc(L.dsspk_conv_fwd(st, X.data_ptr(), W0.data_ptr(), None, c.data_ptr(), N, H, H, C, C, 3, 3, 1, 1, 0, recA.data_ptr()))
+    rc(L.dsspk_conv_fwd_prebn(st, c.data_ptr(), recA.data_ptr(), parts, Ga.data_ptr(), Be.data_ptr(), 1e-5,
+                              SC.data_ptr() if with_sc else None, a.data_ptr(), stats.data_ptr(), W1.data_ptr(), y.data_ptr(),
+                              recB.data_ptr(), N, H, C))
+    co = oracle_nn.conv2d_fwd(x.astype(np.float64), w0.astype(np.float64), None, 1, 1)
+    bo, mean, invstd = oracle_nn.bn_fwd(co, gamma.astype(np.float64), beta.astype(np.float64))
+    ao = np.maximum(bo + (sc if with_sc else 0), 0)
+    yo = oracle_nn.conv2d_fwd(ao, w1.astype(np.float64), None, 1, 1)
+    assert rel_l2(host(stats)[:C], mean) < 5e-6 and rel_l2(host(stats)[C:], invstd) < TOL
+    assert rel_l2(host(a), ao) < 5e-6
+    assert rel_l2(host(y), yo) < 5e-6
+    # the records of y merge to y's statistics
+    out = empty((N, H, H, C)); st2 = empty(2 * C)
+    rc(L.dsspk_bn_fwd(st, y.data_ptr(), Ga.data_ptr(), Be.data_ptr(), out.data_ptr(), st2.data_ptr(), recB.data_ptr(),
+                      M, C, 1e-5, 0, 0, None, 0, 0, 0, parts))
+    _, mean2, invstd2 = oracle_nn.bn_fwd(yo, gamma.astype(np.float64), beta.astype(np.float64))
+    assert rel_l2(host(st2)[:C], mean2) < 2e-5 and rel_l2(host(st2)[C:], invstd2) < 5e-6
+
+
 # ------------------------------------------------------------------ elementwise / pooling
 @pytest.mark.parametrize("n", [5, 64, 100003])
 def test_relu_bwd_and_add(n):
