@@ -39,8 +39,8 @@ struct Cfg {
 // Normalisation applied to the input while it is loaded (PRE != 0): the kernel then computes
 //   a = ReLU(gamma * (src - mean) * invstd + beta (+ shortcut))   and   dst = conv(a),
 // i.e. the batch norm + ReLU that separates two convolutions never runs as a pass of its own.
-// mean / invstd come from the statistics records of src (merged by every workgroup in its
-// prologue); the workgroups also write `a` (their own rows) and mean / invstd for the backward pass.
+// mean / invstd come from the statistics records of src, merged by a one-workgroup kernel launched just
+// before (they are also what the backward pass needs); the workgroups write `a` (their own rows).
 struct PreBn {
     const float* records;      // statistics records of src
     bnm::BnLayout L;           // their layout
@@ -69,40 +69,56 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
     const int r_base = band * R;                    // first output row of the band
     const int co_base = split * K::CN;
 
-    // ---- input halo tile, zero outside the image
+    // ---- input halo tile, zero outside the image.  The raw loads are issued first; with PRE the merge of
+    //      the statistics records (a latency chain of its own) then runs while they are in flight.
     constexpr int V = C / 4;
+    constexpr int NL = ((R + 2) * K::TW * V + THREADS - 1) / THREADS;
     float* Sh = lds + K::XS + K::WS + K::SS + THREADS;       // mean[C], invstd[C] of the input (PRE)
-    if constexpr (PRE != 0) {
-        bnm::bn_merge_stats(pre.records, pre.M, C, pre.eps, lds + K::XS + K::WS + K::SS, Sh, pre.L);
-        if (blockIdx.x == 0 && tid < 2 * C) pre.stats_out[tid] = Sh[tid];
-    }
-    for (int idx = tid; idx < (R + 2) * K::TW * V; idx += THREADS) {
+    float4 val[NL], scv[PRE == 2 ? NL : 1];
+#pragma unroll
+    for (int e = 0; e < NL; ++e) {
+        const int idx = tid + e * THREADS;
         const int v = idx % V;
         const int pc = (idx / V) % K::TW, pr = idx / (V * K::TW);
         const int h = r_base + pr - 1, w = pc - 1;
-        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (h >= 0 && h < HW && w >= 0 && w < HW) {
+        val[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (pr < R + 2 && h >= 0 && h < HW && w >= 0 && w < HW) {
             const long off = (((long)n * HW + h) * HW + w) * C + 4 * v;
-            val = *reinterpret_cast<const float4*>(src + off);
-            if constexpr (PRE != 0) {
+            val[e] = *reinterpret_cast<const float4*>(src + off);
+            if constexpr (PRE == 2) scv[e] = *reinterpret_cast<const float4*>(pre.shortcut + off);
+        }
+    }
+    if constexpr (PRE != 0) {           // mean / invstd of the input, merged from its records by records_merge_kernel
+        if (tid < 2 * C) Sh[tid] = pre.stats_out[tid];
+        __syncthreads();
+    }
+#pragma unroll
+    for (int e = 0; e < NL; ++e) {
+        const int idx = tid + e * THREADS;
+        const int v = idx % V;
+        const int pc = (idx / V) % K::TW, pr = idx / (V * K::TW);
+        const int h = r_base + pr - 1, w = pc - 1;
+        if (pr >= R + 2) continue;
+        if constexpr (PRE != 0) {
+            if (h >= 0 && h < HW && w >= 0 && w < HW) {
                 const float4 mu = *reinterpret_cast<const float4*>(Sh + 4 * v);
                 const float4 is = *reinterpret_cast<const float4*>(Sh + C + 4 * v);
                 const float4 ga = *reinterpret_cast<const float4*>(pre.gamma + 4 * v);
                 const float4 be = *reinterpret_cast<const float4*>(pre.beta + 4 * v);
-                val.x = fmaf((val.x - mu.x) * is.x, ga.x, be.x);
-                val.y = fmaf((val.y - mu.y) * is.y, ga.y, be.y);
-                val.z = fmaf((val.z - mu.z) * is.z, ga.z, be.z);
-                val.w = fmaf((val.w - mu.w) * is.w, ga.w, be.w);
-                if constexpr (PRE == 2) {
-                    const float4 sc = *reinterpret_cast<const float4*>(pre.shortcut + off);
-                    val.x += sc.x; val.y += sc.y; val.z += sc.z; val.w += sc.w;
-                }
-                val.x = fmaxf(val.x, 0.f); val.y = fmaxf(val.y, 0.f); val.z = fmaxf(val.z, 0.f); val.w = fmaxf(val.w, 0.f);
+                float4 o = val[e];
+                o.x = fmaf((o.x - mu.x) * is.x, ga.x, be.x);
+                o.y = fmaf((o.y - mu.y) * is.y, ga.y, be.y);
+                o.z = fmaf((o.z - mu.z) * is.z, ga.z, be.z);
+                o.w = fmaf((o.w - mu.w) * is.w, ga.w, be.w);
+                if constexpr (PRE == 2) { o.x += scv[e].x; o.y += scv[e].y; o.z += scv[e].z; o.w += scv[e].w; }
+                o.x = fmaxf(o.x, 0.f); o.y = fmaxf(o.y, 0.f); o.z = fmaxf(o.z, 0.f); o.w = fmaxf(o.w, 0.f);
+                val[e] = o;
                 // the band's own rows (not the halo rows) are this workgroup's part of `a`
-                if (split == 0 && pr >= 1 && pr <= R) *reinterpret_cast<float4*>(pre.act_out + off) = val;
+                if (split == 0 && pr >= 1 && pr <= R)
+                    *reinterpret_cast<float4*>(pre.act_out + (((long)n * HW + h) * HW + w) * C + 4 * v) = o;
             }
         }
-        *reinterpret_cast<float4*>(&Xs[(pr * K::TW + pc) * K::LDC + 4 * v]) = val;
+        *reinterpret_cast<float4*>(&Xs[(pr * K::TW + pc) * K::LDC + 4 * v]) = val[e];
     }
     // ---- filter slab Ws[tap][j][k]: j = output channel of this kernel, k = reduction channel.
     //      forward : Ws[tap][co][ci] = w[tap][ci][co]          (transposing store)
@@ -212,6 +228,43 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
     }
 }
 
+// Statistics records -> mean[C], invstd[C].  One workgroup per 4 channels, 64 lanes per channel, so a lane
+// fetches at most 8 records (all in flight together) and the kernel is a few microseconds of latency on
+// C/4 CUs; cheaper than letting every workgroup of the consumer repeat the merge.  The arithmetic is the
+// fixed-order merge of bn_merge.hpp: mean = sum n_g mean_g / M, M2 = sum (M2_g + n_g (mean_g - mean)^2).
+__global__ __launch_bounds__(THREADS) void records_merge_kernel(const float* __restrict__ records, int G, long rows_per_record,
+                                                                long M, int C, float eps, float* __restrict__ stats) {
+    __shared__ float red[THREADS];
+    constexpr int CW = 4, SUB = THREADS / CW;
+    const int cl = threadIdx.x % CW, sub = threadIdx.x / CW;
+    const int c = blockIdx.x * CW + cl;
+    float2 pv[8];
+    float nn[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int g = sub + u * SUB;
+        const int gc = min(g, G - 1);
+        pv[u] = *reinterpret_cast<const float2*>(records + ((long)gc * C + c) * 2);
+        const long lo = (long)gc * rows_per_record;
+        nn[u] = g < G ? (float)(min(M, lo + rows_per_record) - lo) : 0.f;
+    }
+    float s_ = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s_ = fmaf(nn[u], pv[u].x, s_);
+    const float mean = bnm::reduce_sub(s_, red, cl, sub, SUB, CW) / (float)M;
+    float m2 = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const float d = pv[u].x - mean;
+        m2 += nn[u] > 0.f ? pv[u].y + nn[u] * d * d : 0.f;
+    }
+    m2 = bnm::reduce_sub(m2, red, cl, sub, SUB, CW);
+    if (sub == 0) {
+        stats[c] = mean;
+        stats[C + c] = 1.0f / sqrtf(m2 / (float)M + eps);
+    }
+}
+
 template <int C, int HW, int R, int NSPLIT, bool T, int PRE = 0>
 int launch(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial, int N,
            const PreBn& pre = PreBn()) {
@@ -254,6 +307,9 @@ int conv3x3_direct_prebn(hipStream_t s, const float* src, const float* records, 
     pre.L.rows_per_block = pre.M / in_parts;
     pre.gamma = gamma; pre.beta = beta; pre.eps = eps;
     pre.shortcut = shortcut; pre.act_out = act_out; pre.stats_out = stats_out;
+    if (C != 16 && C != 32 && C != 64) return -2;
+    if (in_parts > 8 * (THREADS / 4)) return -1;
+    hipLaunchKernelGGL(records_merge_kernel, dim3(C / 4), dim3(THREADS), 0, s, records, in_parts, pre.L.rows_per_block, pre.M, C, eps, stats_out);
     if (C == 16 && HW == 32)
         return shortcut ? launch<16, 32, 8, 1, false, 2>(s, src, w, nullptr, dst, bn_partial, N, pre)
                         : launch<16, 32, 8, 1, false, 1>(s, src, w, nullptr, dst, bn_partial, N, pre);
