@@ -55,6 +55,15 @@ int dsspk_conv_fwd_prebn(void* stream, const float* src_dev, const float* record
  * is not NULL (the gradient arriving through a residual shortcut; add_dev has dx's shape, may not alias dx). */
 int dsspk_conv_bwd_data(void* stream, const float* dy_dev, const float* w_dev, const float* add_dev, float* dx_dev,
                         int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad);
+/* 3x3 / stride 1 / pad 1 / C -> C only (shapes with dsspk_conv_fwd_stat_parts > 0, -1 otherwise): d-input as
+ * above, then in the same kernel the first half of the backward pass of the ReLU + batch norm whose output fed
+ * this convolution: dz = (dx + add) * [mask_src > 0] is what is stored to dz_dev, and per tile and channel
+ * (sum dz, sum dz * xhat), xhat = (xc - mean) * invstd with mean / invstd from stats_dev, go to records_dev
+ * (dsspk_conv_fwd_stat_parts(...) records; consumed by dsspk_bn_bwd_dx with conv_parts).  mask_src_dev: the
+ * saved post-ReLU activation, xc_dev: that batch norm's input; both have dx's shape. */
+int dsspk_conv_bwd_data_post(void* stream, const float* dy_dev, const float* w_dev, const float* add_dev, float* dz_dev,
+                             const float* mask_src_dev, const float* xc_dev, const float* stats_dev, float* records_dev,
+                             int N, int H, int C);
 /* dw[kh][kw][ci][co] = sum over batch and output pixels of x * dy.  Two stages (partial sums per
  * pixel chunk, then a fixed-order reduction).  scratch_dev: dsspk_conv_wgrad_scratch_floats(...) floats. */
 int dsspk_conv_bwd_weight(void* stream, const float* x_dev, const float* dy_dev, float* dw_dev, float* scratch_dev,
@@ -92,8 +101,9 @@ int dsspk_bn_bwd(void* stream, const float* x_dev, const float* gamma_dev, const
 /* The two kernels of dsspk_bn_bwd on their own: the per-slab sums (and the ReLU mask written into da), then dx. */
 int dsspk_bn_bwd_reduce(void* stream, const float* x_dev, const float* stats_dev, float* da_dev, const float* out_dev,
                         float* scratch_dev, long M, int C);
+/* conv_parts > 0: scratch_dev holds that many (sum dz, sum dz*xhat) records written by dsspk_conv_bwd_data_post. */
 int dsspk_bn_bwd_dx(void* stream, const float* x_dev, const float* gamma_dev, const float* stats_dev, const float* dz_dev,
-                    float* dx_dev, float* dgamma_dev, float* dbeta_dev, const float* scratch_dev, long M, int C);
+                    float* dx_dev, float* dgamma_dev, float* dbeta_dev, const float* scratch_dev, long M, int C, int conv_parts);
 size_t dsspk_bn_scratch_floats(long M, int C);
 
 /* dx[n][2ho][2wo][c] += dy[n][ho][wo][c] for c < C/2 (transpose of shortcut_mode 2). */

@@ -74,7 +74,8 @@ _SIGNATURES = {
     "dsspk_bn_fwd": (c_int, [c_void_p] * 7 + [c_long, c_int, c_float, c_int, c_int, c_void_p, c_int, c_int, c_int, c_int]),
     "dsspk_bn_bwd": (c_int, [c_void_p] * 10 + [c_long, c_int]),
     "dsspk_bn_bwd_reduce": (c_int, [c_void_p] * 6 + [c_long, c_int]),
-    "dsspk_bn_bwd_dx": (c_int, [c_void_p] * 9 + [c_long, c_int]),
+    "dsspk_bn_bwd_dx": (c_int, [c_void_p] * 9 + [c_long, c_int, c_int]),
+    "dsspk_conv_bwd_data_post": (c_int, [c_void_p] * 9 + [c_int] * 3),
     "dsspk_bn_scratch_floats": (c_size_t, [c_long, c_int]),
     "dsspk_shortcut_bwd_acc": (c_int, [c_void_p] * 3 + [c_int] * 4),
     "dsspk_gap_fwd": (c_int, [c_void_p] * 3 + [c_int] * 3),

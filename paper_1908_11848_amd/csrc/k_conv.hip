@@ -17,6 +17,8 @@
 int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial,
                    int N, int HW, int C, bool transposed);
 int conv3x3_direct_stat_parts(int N, int HW, int C);
+int conv3x3_direct_dgrad_post(hipStream_t s, const float* dy, const float* w, const float* add, float* dz,
+                              const float* mask_src, const float* xc, const float* stats, float* records, int N, int HW, int C);
 int conv3x3_direct_prebn(hipStream_t s, const float* src, const float* records, int in_parts, const float* gamma,
                          const float* beta, float eps, const float* shortcut, float* act_out, float* stats_out,
                          const float* w, float* dst, float* bn_partial, int N, int HW, int C);
@@ -487,6 +489,14 @@ extern "C" int dsspk_conv_fwd_prebn(void* stream, const float* src, const float*
     if (conv3x3_direct_stat_parts(N, H, C) == 0) return -1;
     const int rc = conv3x3_direct_prebn((hipStream_t)stream, src, records, in_parts, gamma, beta, eps, shortcut, act_out, stats_out,
                                         w, y, bn_partial, N, H, C);
+    return rc == -2 ? -1 : rc;
+}
+
+extern "C" int dsspk_conv_bwd_data_post(void* stream, const float* dy, const float* w, const float* add, float* dz,
+                                        const float* mask_src, const float* xc, const float* stats, float* records,
+                                        int N, int H, int C) {
+    if (!dy || !w || !dz || !mask_src || !xc || !stats || !records || N < 1) return -1;
+    const int rc = conv3x3_direct_dgrad_post((hipStream_t)stream, dy, w, add, dz, mask_src, xc, stats, records, N, H, C);
     return rc == -2 ? -1 : rc;
 }
 

@@ -30,7 +30,7 @@ struct Cfg {
     static constexpr int RUNS = R * HW / 16;       // 16-pixel runs in the band
     static constexpr int WM = RUNS / 4;            // runs per wavefront
     static constexpr int WN = CN / 16;
-    static constexpr int SS = 4 * CN;              // per-wavefront column sums (batch-norm statistics)
+    static constexpr int SS = 8 * CN;              // per-wavefront column sums (batch-norm records, two components)
     static constexpr int PS = THREADS + 2 * C;     // merge of the input's batch-norm records: tree + (mean, invstd)
     static constexpr size_t LDS_BYTES = (size_t)(XS + WS + SS + PS) * sizeof(float);
     static_assert(RUNS % 4 == 0 && WM >= 1, "band must give every wavefront at least one run");
@@ -53,10 +53,21 @@ struct PreBn {
     float* stats_out;          // mean[C], invstd[C]
 };
 
-template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED, int PRE>
+// Backward of the ReLU + batch norm that FOLLOWS in the backward direction, started in the epilogue (POST):
+// the result r (gradient w.r.t. a post-ReLU activation) is masked, dz = r * [mask_src > 0], dz is what gets
+// stored, and the per-tile sums (sum dz, sum dz * xhat) with xhat = (xc - mean) * invstd are written as
+// records for the batch norm's dx kernel.  This replaces that batch norm's stand-alone reduction pass.
+struct PostBn {
+    const float* mask_src;     // the saved post-ReLU activation
+    const float* xc;           // the batch norm's input (convolution output)
+    const float* stats;        // its mean[C], invstd[C]
+    float* records;            // out: (sum dz, sum dz * xhat) per tile and channel
+};
+
+template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED, int PRE, bool POST = false>
 __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
                                                           const float* __restrict__ add, float* __restrict__ dst,
-                                                          float* __restrict__ bn_partial, PreBn pre) {
+                                                          float* __restrict__ bn_partial, PreBn pre, PostBn post) {
     using K = Cfg<C, HW, R, NSPLIT>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float* Xs = lds;
@@ -178,6 +189,15 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
 
     mma::drain();
     // ---- store: lane holds rows 4q..4q+3 (pixels of the run) of column l16
+    float sum_dz[K::WN], sum_dzx[K::WN], mu_c[K::WN], is_c[K::WN];
+    if constexpr (POST) {
+#pragma unroll
+        for (int wn = 0; wn < K::WN; ++wn) {
+            sum_dz[wn] = 0.f; sum_dzx[wn] = 0.f;
+            mu_c[wn] = post.stats[co_base + 16 * wn + l16];
+            is_c[wn] = post.stats[C + co_base + 16 * wn + l16];
+        }
+    }
 #pragma unroll
     for (int wm = 0; wm < K::WM; ++wm) {
         const int run = wave * K::WM + wm;
@@ -187,7 +207,37 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
             const int h = r_base + p / HW, w = p % HW;
             const long off = (((long)n * HW + h) * HW + w) * C + co_base + l16;
 #pragma unroll
-            for (int wn = 0; wn < K::WN; ++wn) dst[off + 16 * wn] = acc[wm][wn][v] + (add ? add[off + 16 * wn] : 0.f);
+            for (int wn = 0; wn < K::WN; ++wn) {
+                float r = acc[wm][wn][v] + (add ? add[off + 16 * wn] : 0.f);
+                if constexpr (POST) {
+                    r = post.mask_src[off + 16 * wn] > 0.f ? r : 0.f;
+                    const float xh = (post.xc[off + 16 * wn] - mu_c[wn]) * is_c[wn];
+                    sum_dz[wn] += r;
+                    sum_dzx[wn] = fmaf(r, xh, sum_dzx[wn]);
+                }
+                dst[off + 16 * wn] = r;
+            }
+        }
+    }
+    if constexpr (POST) {
+        float* Ss = lds + K::XS + K::WS;
+#pragma unroll
+        for (int wn = 0; wn < K::WN; ++wn) {
+            float a_ = sum_dz[wn], b_ = sum_dzx[wn];
+            a_ += __shfl_xor(a_, 16); a_ += __shfl_xor(a_, 32);
+            b_ += __shfl_xor(b_, 16); b_ += __shfl_xor(b_, 32);
+            if (q == 0) { Ss[wave * K::CN + 16 * wn + l16] = a_; Ss[4 * K::CN + wave * K::CN + 16 * wn + l16] = b_; }
+        }
+        __syncthreads();
+        if (wave == 0 && q == 0) {
+#pragma unroll
+            for (int wn = 0; wn < K::WN; ++wn) {
+                const int c = 16 * wn + l16;
+                const float ta = (Ss[c] + Ss[K::CN + c]) + (Ss[2 * K::CN + c] + Ss[3 * K::CN + c]);
+                const float* Sb = Ss + 4 * K::CN;
+                const float tb = (Sb[c] + Sb[K::CN + c]) + (Sb[2 * K::CN + c] + Sb[3 * K::CN + c]);
+                *reinterpret_cast<float2*>(post.records + ((long)(n * BANDS + band) * C + co_base + c) * 2) = make_float2(ta, tb);
+            }
         }
     }
 
@@ -265,19 +315,19 @@ __global__ __launch_bounds__(THREADS) void records_merge_kernel(const float* __r
     }
 }
 
-template <int C, int HW, int R, int NSPLIT, bool T, int PRE = 0>
+template <int C, int HW, int R, int NSPLIT, bool T, int PRE = 0, bool POST = false>
 int launch(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial, int N,
-           const PreBn& pre = PreBn()) {
+           const PreBn& pre = PreBn(), const PostBn& post = PostBn()) {
     using K = Cfg<C, HW, R, NSPLIT>;
     static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
-    auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T, PRE>;
+    auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T, PRE, POST>;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)K::LDS_BYTES) != hipSuccess)
             return -1;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst, bn_partial, pre);
+    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst, bn_partial, pre, post);
     return DSSPK_LAUNCH_RC();
 }
 
@@ -319,6 +369,18 @@ int conv3x3_direct_prebn(hipStream_t s, const float* src, const float* records, 
     if (C == 64 && HW == 8)
         return shortcut ? launch<64, 8, 8, 2, false, 2>(s, src, w, nullptr, dst, bn_partial, N, pre)
                         : launch<64, 8, 8, 2, false, 1>(s, src, w, nullptr, dst, bn_partial, N, pre);
+    return -2;
+}
+
+// d-input of the convolution (+ add) followed, in the same kernel, by the ReLU mask and the record sums of the
+// batch norm that comes next in the backward direction, see PostBn.
+int conv3x3_direct_dgrad_post(hipStream_t s, const float* dy, const float* w, const float* add, float* dz,
+                              const float* mask_src, const float* xc, const float* stats, float* records, int N, int HW, int C) {
+    PostBn post;
+    post.mask_src = mask_src; post.xc = xc; post.stats = stats; post.records = records;
+    if (C == 16 && HW == 32) return launch<16, 32, 8, 1, true, 0, true>(s, dy, w, add, dz, nullptr, N, PreBn(), post);
+    if (C == 32 && HW == 16) return launch<32, 16, 8, 1, true, 0, true>(s, dy, w, add, dz, nullptr, N, PreBn(), post);
+    if (C == 64 && HW == 8) return launch<64, 8, 8, 2, true, 0, true>(s, dy, w, add, dz, nullptr, N, PreBn(), post);
     return -2;
 }
 

@@ -474,10 +474,16 @@ extern "C" int dsspk_bn_bwd_reduce(void* stream, const float* x, const float* st
 }
 
 extern "C" int dsspk_bn_bwd_dx(void* stream, const float* x, const float* gamma, const float* stats, const float* dz,
-                               float* dx, float* dgamma, float* dbeta, const float* scratch, long M, int C) {
+                               float* dx, float* dgamma, float* dbeta, const float* scratch, long M, int C, int conv_parts) {
     if (!bn_bwd_args_ok(x, gamma, stats, dz, nullptr, dx, dgamma, dbeta, scratch, M, C)) return -1;
+    BnLayout Lr = bn_layout(M, C);
+    if (conv_parts > 0) {           // records written by a convolution epilogue, one per tile
+        if (M % conv_parts || conv_parts > 32 * (THREADS / C)) return -1;
+        Lr.G = conv_parts;
+        Lr.rows_per_block = M / conv_parts;
+    }
     hipLaunchKernelGGL(bn_bwd_dx_kernel, dim3(bn_elem_grid(M, C)), dim3(THREADS), 0, (hipStream_t)stream,
-                       x, gamma, stats, dz, scratch, dgamma, dbeta, dx, M, C, bn_layout(M, C));
+                       x, gamma, stats, dz, scratch, dgamma, dbeta, dx, M, C, Lr);
     return DSSPK_LAUNCH_RC();
 }
 
@@ -485,7 +491,7 @@ extern "C" int dsspk_bn_bwd(void* stream, const float* x, const float* gamma, co
                             const float* out, float* dx, float* dgamma, float* dbeta, float* scratch, long M, int C) {
     if (!bn_bwd_args_ok(x, gamma, stats, da, out, dx, dgamma, dbeta, scratch, M, C)) return -1;
     if (int rc = dsspk_bn_bwd_reduce(stream, x, stats, da, out, scratch, M, C)) return rc;
-    return dsspk_bn_bwd_dx(stream, x, gamma, stats, da, dx, dgamma, dbeta, scratch, M, C);
+    return dsspk_bn_bwd_dx(stream, x, gamma, stats, da, dx, dgamma, dbeta, scratch, M, C, 0);
 }
 
 extern "C" int dsspk_shortcut_bwd_acc(void* stream, const float* dy, float* dx, int N, int Ho, int Wo, int C) {

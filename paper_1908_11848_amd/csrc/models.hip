@@ -276,26 +276,49 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
     RUN(dsspk_gemm(s, F(P->dlogits), C, 1, w + P->fc_w, 1, C, F(P->dpooled), 64, m, 64, C, nullptr, 0));
     float *g0 = F(P->G[0]), *g1 = F(P->G[1]), *g2 = F(P->G[2]);     // g0: gradient w.r.t. the current block output
     RUN(dsspk_gap_bwd(s, F(P->dpooled), g0, m, 64, 64));
+    // Where a d-input convolution of the direct 3x3 kind produces the gradient of a post-ReLU activation, its
+    // epilogue also applies the ReLU mask and writes the sum records of the batch norm behind it, so that batch
+    // norm's backward pass starts at its dx kernel.  parts0 > 0: g0 already holds the masked dz of this block's
+    // BN2 and recB0 its records; 0: the stand-alone reduction kernel does both.
+    float* recB0 = F(P->bn_scratch2);
+    int parts0 = 0;
     for (int bi = (int)P->blocks.size() - 1; bi >= 0; --bi) {
         const ResBlock& B = P->blocks[bi];
         const float* xin = bi ? F(P->blocks[bi - 1].out) : F(P->stem_a);
         const int Ho = B.H / B.stride;
         const long M = (long)m * Ho * Ho;
-        // g0 <- dz2 = g0 * [out > 0];  g1 <- d conv2 output
-        RUN(dsspk_bn_bwd(s, F(B.c2), w + B.g2, F(B.st2), g0, F(B.out), g1, g + B.g2, g + B.b2, bscr, M, B.cout));
+        // ---- BN2: g0 <- dz2 = g0 * [out > 0] (unless done already); g1 <- d conv2 output
+        if (!parts0) RUN(dsspk_bn_bwd_reduce(s, F(B.c2), F(B.st2), g0, F(B.out), recB0, M, B.cout));
+        RUN(dsspk_bn_bwd_dx(s, F(B.c2), w + B.g2, F(B.st2), g0, g1, g + B.g2, g + B.b2, recB0, M, B.cout, parts0));
         RUN(dsspk_conv_bwd_weight(s, F(B.a1), g1, g + B.w2, scr, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));
-        RUN(dsspk_conv_bwd_data(s, g1, w + B.w2, nullptr, g2, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));      // g2 <- d a1
-        // g2 <- dz1 = g2 * [a1 > 0];  g1 <- d conv1 output
-        RUN(dsspk_bn_bwd(s, F(B.c1), w + B.g1, F(B.st1), g2, F(B.a1), g1, g + B.g1, g + B.b1, bscr, M, B.cout));
+        // ---- conv2 d-input -> g2 = dz1 = d a1 * [a1 > 0], with BN1's sum records where the direct kernel applies
+        const int parts1 = dsspk_conv_fwd_stat_parts(m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1);
+        if (parts1) {
+            RUN(dsspk_conv_bwd_data_post(s, g1, w + B.w2, nullptr, g2, F(B.a1), F(B.c1), F(B.st1), bscr, m, Ho, B.cout));
+        } else {
+            RUN(dsspk_conv_bwd_data(s, g1, w + B.w2, nullptr, g2, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));
+            RUN(dsspk_bn_bwd_reduce(s, F(B.c1), F(B.st1), g2, F(B.a1), bscr, M, B.cout));
+        }
+        RUN(dsspk_bn_bwd_dx(s, F(B.c1), w + B.g1, F(B.st1), g2, g1, g + B.g1, g + B.b1, bscr, M, B.cout, parts1));
         RUN(dsspk_conv_bwd_weight(s, xin, g1, g + B.w1, scr, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1));
-        // g2 <- d xin: the conv path plus, for an identity shortcut, dz2 (added in the kernel's epilogue)
+        // ---- conv1 d-input (+ dz2 through an identity shortcut) -> g2 = gradient w.r.t. the block's input, which
+        //      is the previous block's (or the stem's) post-ReLU output: mask + records of ITS batch norm here too
         const bool identity = B.stride == 1 && B.cin == B.cout;
-        RUN(dsspk_conv_bwd_data(s, g1, w + B.w1, identity ? g0 : nullptr, g2, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1));
-        if (!identity) RUN(dsspk_shortcut_bwd_acc(s, g0, g2, m, Ho, Ho, B.cout));
+        const int partsp = identity ? dsspk_conv_fwd_stat_parts(m, B.H, B.H, B.cin, B.cout, 3, 3, 1, 1) : 0;
+        if (partsp) {
+            const float* pc = bi ? F(P->blocks[bi - 1].c2) : F(P->stem_c);
+            const float* pst = bi ? F(P->blocks[bi - 1].st2) : F(P->stem_st);
+            RUN(dsspk_conv_bwd_data_post(s, g1, w + B.w1, g0, g2, xin, pc, pst, recB0, m, B.H, B.cin));
+        } else {
+            RUN(dsspk_conv_bwd_data(s, g1, w + B.w1, identity ? g0 : nullptr, g2, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1));
+            if (!identity) RUN(dsspk_shortcut_bwd_acc(s, g0, g2, m, Ho, Ho, B.cout));
+        }
+        parts0 = partsp;
         float* t = g0; g0 = g2; g2 = t;
     }
-    RUN(dsspk_bn_bwd(s, F(P->stem_c), w + P->stem_g, F(P->stem_st), g0, F(P->stem_a), g1, g + P->stem_g, g + P->stem_b,
-                     bscr, (long)m * 1024, 16));
+    if (!parts0) RUN(dsspk_bn_bwd_reduce(s, F(P->stem_c), F(P->stem_st), g0, F(P->stem_a), recB0, (long)m * 1024, 16));
+    RUN(dsspk_bn_bwd_dx(s, F(P->stem_c), w + P->stem_g, F(P->stem_st), g0, g1, g + P->stem_g, g + P->stem_b, recB0,
+                        (long)m * 1024, 16, parts0));
     RUN(dsspk_conv_bwd_weight(s, x, g1, g + P->stem_w, scr, m, 32, 32, 3, 16, 3, 3, 1, 1));
     return 0;
 }

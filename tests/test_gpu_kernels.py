@@ -183,6 +183,41 @@ def test_conv_with_batchnorm_folded_into_its_loader(oracle_nn, N, H, C, with_sc)
     assert rel_l2(host(st2)[:C], mean2) < 2e-5 and rel_l2(host(st2)[C:], invstd2) < 5e-6
 
 
+@pytest.mark.parametrize("N,H,C,with_add", [(3, 32, 16, True), (5, 16, 32, False), (4, 8, 64, True), (128, 16, 32, True)])
+def test_dgrad_with_relu_mask_and_batchnorm_records(oracle_nn, N, H, C, with_add):
+    """d-input convolution whose epilogue masks by the saved activation and emits the sum records of the batch
+    norm behind it; followed by that batch norm's dx kernel.  Against: oracle d-input, mask, oracle BN backward."""
+    g = np.random.default_rng(N * 11 + H + C)
+    M = N * H * H
+    dy, w = f32(g, (N, H, H, C)), f32(g, (3, 3, C, C), (2.0 / (9 * C)) ** 0.5)
+    add = f32(g, (N, H, H, C)) if with_add else None
+    xc = f32(g, (N, H, H, C), 2.0) + np.float32(0.5)                    # the batch norm's input
+    gamma, beta = (1 + 0.2 * g.standard_normal(C)).astype(np.float32), f32(g, C, 0.3)
+    L = B.lib()
+    st = stream_ptr()
+    parts = L.dsspk_conv_fwd_stat_parts(N, H, H, C, C, 3, 3, 1, 1)
+    XC, Ga, Be, DY, W = dev(xc), dev(gamma), dev(beta), dev(dy), dev(w)
+    ADD = dev(add) if with_add else None
+    act = empty((N, H, H, C)); stats = empty(2 * C); rec = empty(L.dsspk_bn_scratch_floats(M, C))
+    rc(L.dsspk_bn_fwd(st, XC.data_ptr(), Ga.data_ptr(), Be.data_ptr(), act.data_ptr(), stats.data_ptr(), rec.data_ptr(),
+                      M, C, 1e-5, 1, 0, None, 0, 0, 0, 0))                # forward: act = ReLU(BN(xc)), saves mean / invstd
+    dz = empty((N, H, H, C)); dx = empty((N, H, H, C)); dgam = empty(C); dbet = empty(C)
+    rc(L.dsspk_conv_bwd_data_post(st, DY.data_ptr(), W.data_ptr(), ADD.data_ptr() if with_add else None, dz.data_ptr(),
+                                  act.data_ptr(), XC.data_ptr(), stats.data_ptr(), rec.data_ptr(), N, H, C))
+    rc(L.dsspk_bn_bwd_dx(st, XC.data_ptr(), Ga.data_ptr(), stats.data_ptr(), dz.data_ptr(), dx.data_ptr(), dgam.data_ptr(),
+                         dbet.data_ptr(), rec.data_ptr(), M, C, parts))
+    x64 = np.zeros((N, H, H, C))
+    dxo, _, _ = oracle_nn.conv2d_bwd(x64, w.astype(np.float64), dy.astype(np.float64), 1, 1, False)
+    r = dxo + (add if with_add else 0)
+    mask = host(act) > 0                                               # decisions of the forward pass (same bits on both sides)
+    dzo = np.where(mask, r, 0)
+    assert rel_l2(host(dz), dzo) < TOL
+    _, mean, invstd = oracle_nn.bn_fwd(xc.astype(np.float64), gamma.astype(np.float64), beta.astype(np.float64))
+    dxb, dgo, dbo = oracle_nn.bn_bwd(xc.astype(np.float64), gamma.astype(np.float64), mean, invstd, dzo)
+    assert rel_l2(host(dgam), dgo) < 5e-6 and rel_l2(host(dbet), dbo) < 5e-6
+    assert rel_l2(host(dx), dxb) < 5e-6
+
+
 # ------------------------------------------------------------------ elementwise / pooling
 @pytest.mark.parametrize("n", [5, 64, 100003])
 def test_relu_bwd_and_add(n):
