@@ -3,15 +3,18 @@
 //
 // A workgroup owns a band of R output rows of one image (the whole 8x8 image in the last
 // stage) and CN of the C output channels.  It loads the (R+2) x (HW+2) x C input halo tile
-// (zero borders) and its 9 x C x CN filter slab into LDS once; all nine taps are then served
-// from LDS, so every input element is read from memory once per band instead of nine times.
+// (zero borders) into LDS once; all nine taps are then served from LDS, so every input element
+// is read from memory once per band instead of nine times.  The filter never passes through
+// LDS: a wavefront owns ONE tile of 16 output channels and keeps that tile's 9 x C filter
+// values in registers (9 * C / 16 float4 per lane, fetched straight from the cached filter
+// while the halo tile is still in flight).  LDS therefore holds the halo tile only (about
+// 27 KB in every stage), which lets workgroups of several kernels share a compute unit.
 // Matrix-core tiles are 16 pixels (a run along the image row; two 8-pixel rows in the last
 // stage) x 16 output channels, v_mfma_f32_16x16x4_f32, with the k-permutation of mma.hpp: both
-// operands are k-contiguous in LDS, so each lane feeds four MFMAs from one 16-byte read per
-// operand.
+// operands are k-contiguous per lane, so one 16-byte LDS read per run feeds four MFMAs.
 //
 // Gradient w.r.t. the input of such a convolution is the same operation on dy with the filter
-// taps reversed and its two channel indices swapped; only the filter load differs.
+// taps reversed and its two channel indices swapped; only the filter fetch differs.
 #include "mma.hpp"
 #include "bn_merge.hpp"
 #include "../../include/dssp_kernels.h"
@@ -23,17 +26,19 @@ constexpr int THREADS = 256;
 template <int C, int HW, int R, int NSPLIT>
 struct Cfg {
     static constexpr int CN = C / NSPLIT;          // output channels per workgroup
-    static constexpr int LDC = C + 4;              // pitch of one pixel / one filter row in LDS (floats)
+    static constexpr int LDC = C + 4;              // pitch of one pixel in LDS (floats)
     static constexpr int TW = HW + 2;              // halo tile width
     static constexpr int XS = (R + 2) * TW * LDC;  // floats
-    static constexpr int WS = 9 * CN * LDC;        // filter slab [tap][co][ci], ci contiguous
     static constexpr int RUNS = R * HW / 16;       // 16-pixel runs in the band
-    static constexpr int WM = RUNS / 4;            // runs per wavefront
-    static constexpr int WN = CN / 16;
+    static constexpr int WAVES_N = CN / 16;        // wavefronts side by side over the output channels
+    static constexpr int WAVES_M = 4 / WAVES_N;    // ... and over the runs
+    static constexpr int WM = RUNS / WAVES_M;      // runs per wavefront
+    static constexpr int KC = C / 16;              // 16-wide chunks of the reduction channel
     static constexpr int SS = 8 * CN;              // per-wavefront column sums (batch-norm records, two components)
     static constexpr int PS = THREADS + 2 * C;     // merge of the input's batch-norm records: tree + (mean, invstd)
-    static constexpr size_t LDS_BYTES = (size_t)(XS + WS + SS + PS) * sizeof(float);
-    static_assert(RUNS % 4 == 0 && WM >= 1, "band must give every wavefront at least one run");
+    static constexpr size_t LDS_BYTES = (size_t)(XS + SS + PS) * sizeof(float);
+    static_assert(WAVES_N == 1 || WAVES_N == 2 || WAVES_N == 4, "one 16-channel tile per wavefront");
+    static_assert(RUNS % WAVES_M == 0 && WM >= 1, "band must give every wavefront at least one run");
 };
 
 // Normalisation applied to the input while it is loaded (PRE != 0): the kernel then computes
@@ -71,20 +76,38 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
     using K = Cfg<C, HW, R, NSPLIT>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float* Xs = lds;
-    float* Ws = lds + K::XS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, q = lane >> 4;
+    const int wave_n = wave % K::WAVES_N, wave_m = wave / K::WAVES_N;
     constexpr int BANDS = HW / R;
     const int split = blockIdx.x % NSPLIT;
     const int band = (blockIdx.x / NSPLIT) % BANDS;
     const int n = blockIdx.x / (NSPLIT * BANDS);
     const int r_base = band * R;                    // first output row of the band
     const int co_base = split * K::CN;
+    const int co = co_base + 16 * wave_n + l16;     // this lane's output channel (column of the MFMA tile)
+
+    // ---- filter values of this wavefront's 16 output channels, B[k][co] with k = 16 kc + 4 q + {0..3}:
+    //      forward : w[tap][k][co]           (four loads, C floats apart)
+    //      d-input : w[8 - tap][co][k]       (one 16-byte load, taps reversed)
+    float4 bf[9][K::KC];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+        for (int kc = 0; kc < K::KC; ++kc) {
+            if constexpr (TRANSPOSED) {
+                bf[tap][kc] = *reinterpret_cast<const float4*>(wgt + ((long)(8 - tap) * C + co) * C + 16 * kc + 4 * q);
+            } else {
+                const float* wp = wgt + ((long)tap * C + 16 * kc + 4 * q) * C + co;
+                bf[tap][kc] = make_float4(wp[0], wp[C], wp[2 * C], wp[3 * C]);
+            }
+        }
 
     // ---- input halo tile, zero outside the image.  The raw loads are issued first; with PRE the merge of
     //      the statistics records (a latency chain of its own) then runs while they are in flight.
     constexpr int V = C / 4;
     constexpr int NL = ((R + 2) * K::TW * V + THREADS - 1) / THREADS;
-    float* Sh = lds + K::XS + K::WS + K::SS + THREADS;       // mean[C], invstd[C] of the input (PRE)
+    float* Sh = lds + K::XS + K::SS + THREADS;       // mean[C], invstd[C] of the input (PRE)
     float4 val[NL], scv[PRE == 2 ? NL : 1];
 #pragma unroll
     for (int e = 0; e < NL; ++e) {
@@ -131,35 +154,16 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
         }
         *reinterpret_cast<float4*>(&Xs[(pr * K::TW + pc) * K::LDC + 4 * v]) = val[e];
     }
-    // ---- filter slab Ws[tap][j][k]: j = output channel of this kernel, k = reduction channel.
-    //      forward : Ws[tap][co][ci] = w[tap][ci][co]          (transposing store)
-    //      d-input : Ws[tap][ci][co] = w[8 - tap][ci][co]      (straight copy, taps reversed)
-    if constexpr (!TRANSPOSED) {
-        for (int idx = tid; idx < 9 * C * (K::CN / 4); idx += THREADS) {
-            const int j4 = idx % (K::CN / 4);
-            const int k = (idx / (K::CN / 4)) % C, tap = idx / ((K::CN / 4) * C);
-            const float4 val = *reinterpret_cast<const float4*>(wgt + ((long)tap * C + k) * C + co_base + 4 * j4);
-            float* o = &Ws[(tap * K::CN + 4 * j4) * K::LDC + k];
-            o[0] = val.x; o[K::LDC] = val.y; o[2 * K::LDC] = val.z; o[3 * K::LDC] = val.w;
-        }
-    } else {
-        for (int idx = tid; idx < 9 * K::CN * V; idx += THREADS) {
-            const int v = idx % V;
-            const int j = (idx / V) % K::CN, tap = idx / (V * K::CN);
-            const float4 val = *reinterpret_cast<const float4*>(wgt + ((long)(8 - tap) * C + co_base + j) * C + 4 * v);
-            *reinterpret_cast<float4*>(&Ws[(tap * K::CN + j) * K::LDC + 4 * v]) = val;
-        }
-    }
     __syncthreads();
 
-    // ---- 9 taps x C/16 k-chunks from LDS
-    floatx4 acc[K::WM][K::WN];
-    mma::zero(acc);
-    const int l16 = lane & 15, q = lane >> 4;
+    // ---- 9 taps x C/16 k-chunks: A from LDS, B from registers
+    floatx4 acc[K::WM];
+#pragma unroll
+    for (int wm = 0; wm < K::WM; ++wm) acc[wm] = floatx4{0.f, 0.f, 0.f, 0.f};
     int pix_off[K::WM];                             // LDS offset of this lane's pixel for tap (0,0)
 #pragma unroll
     for (int wm = 0; wm < K::WM; ++wm) {
-        const int run = wave * K::WM + wm;
+        const int run = wave_m * K::WM + wm;
         const int p = run * 16 + l16;               // pixel index inside the band, row-major
         pix_off[wm] = ((p / HW) * K::TW + (p % HW)) * K::LDC + 4 * q;
     }
@@ -167,112 +171,93 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
     for (int tap = 0; tap < 9; ++tap) {
         const int toff = ((tap / 3) * K::TW + (tap % 3)) * K::LDC;
 #pragma unroll
-        for (int kc = 0; kc < C / 16; ++kc) {
-            float4 a[K::WM], b[K::WN];
+        for (int kc = 0; kc < K::KC; ++kc) {
+            float4 a[K::WM];
 #pragma unroll
             for (int wm = 0; wm < K::WM; ++wm)
                 a[wm] = *reinterpret_cast<const float4*>(&Xs[pix_off[wm] + toff + 16 * kc]);
+            const float4 b = bf[tap][kc];
 #pragma unroll
-            for (int wn = 0; wn < K::WN; ++wn)
-                b[wn] = *reinterpret_cast<const float4*>(&Ws[(tap * K::CN + 16 * wn + l16) * K::LDC + 16 * kc + 4 * q]);
+            for (int wm = 0; wm < K::WM; ++wm) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].x, b.x, acc[wm], 0, 0, 0);
 #pragma unroll
-            for (int wm = 0; wm < K::WM; ++wm)
+            for (int wm = 0; wm < K::WM; ++wm) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].y, b.y, acc[wm], 0, 0, 0);
 #pragma unroll
-                for (int wn = 0; wn < K::WN; ++wn) {
-                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].x, b[wn].x, acc[wm][wn], 0, 0, 0);
-                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].y, b[wn].y, acc[wm][wn], 0, 0, 0);
-                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].z, b[wn].z, acc[wm][wn], 0, 0, 0);
-                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].w, b[wn].w, acc[wm][wn], 0, 0, 0);
-                }
+            for (int wm = 0; wm < K::WM; ++wm) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].z, b.z, acc[wm], 0, 0, 0);
+#pragma unroll
+            for (int wm = 0; wm < K::WM; ++wm) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].w, b.w, acc[wm], 0, 0, 0);
         }
     }
 
     mma::drain();
     // ---- store: lane holds rows 4q..4q+3 (pixels of the run) of column l16
-    float sum_dz[K::WN], sum_dzx[K::WN], mu_c[K::WN], is_c[K::WN];
+    float sum_dz = 0.f, sum_dzx = 0.f, mu_c = 0.f, is_c = 0.f;
     if constexpr (POST) {
-#pragma unroll
-        for (int wn = 0; wn < K::WN; ++wn) {
-            sum_dz[wn] = 0.f; sum_dzx[wn] = 0.f;
-            mu_c[wn] = post.stats[co_base + 16 * wn + l16];
-            is_c[wn] = post.stats[C + co_base + 16 * wn + l16];
-        }
+        mu_c = post.stats[co];
+        is_c = post.stats[C + co];
     }
 #pragma unroll
     for (int wm = 0; wm < K::WM; ++wm) {
-        const int run = wave * K::WM + wm;
+        const int run = wave_m * K::WM + wm;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int p = run * 16 + 4 * q + v;
             const int h = r_base + p / HW, w = p % HW;
-            const long off = (((long)n * HW + h) * HW + w) * C + co_base + l16;
-#pragma unroll
-            for (int wn = 0; wn < K::WN; ++wn) {
-                float r = acc[wm][wn][v] + (add ? add[off + 16 * wn] : 0.f);
-                if constexpr (POST) {
-                    r = post.mask_src[off + 16 * wn] > 0.f ? r : 0.f;
-                    const float xh = (post.xc[off + 16 * wn] - mu_c[wn]) * is_c[wn];
-                    sum_dz[wn] += r;
-                    sum_dzx[wn] = fmaf(r, xh, sum_dzx[wn]);
-                }
-                dst[off + 16 * wn] = r;
+            const long off = (((long)n * HW + h) * HW + w) * C + co;
+            float r = acc[wm][v] + (add ? add[off] : 0.f);
+            if constexpr (POST) {
+                r = post.mask_src[off] > 0.f ? r : 0.f;
+                const float xh = (post.xc[off] - mu_c) * is_c;
+                sum_dz += r;
+                sum_dzx = fmaf(r, xh, sum_dzx);
             }
+            dst[off] = r;
         }
     }
+    // per-channel totals over the workgroup's tile: lanes of a wavefront by shuffles, then the WAVES_M
+    // wavefronts that share the channel tile through LDS, in a fixed order
+    float* Ss = lds + K::XS;
+    const int cl = 16 * wave_n + l16;                // channel inside the workgroup's CN
+    auto tile_total = [&](const float* S) {
+        float t = S[cl];
+#pragma unroll
+        for (int m = 1; m < K::WAVES_M; ++m) t += S[m * K::CN + cl];
+        return t;
+    };
     if constexpr (POST) {
-        float* Ss = lds + K::XS + K::WS;
-#pragma unroll
-        for (int wn = 0; wn < K::WN; ++wn) {
-            float a_ = sum_dz[wn], b_ = sum_dzx[wn];
-            a_ += __shfl_xor(a_, 16); a_ += __shfl_xor(a_, 32);
-            b_ += __shfl_xor(b_, 16); b_ += __shfl_xor(b_, 32);
-            if (q == 0) { Ss[wave * K::CN + 16 * wn + l16] = a_; Ss[4 * K::CN + wave * K::CN + 16 * wn + l16] = b_; }
-        }
+        float a_ = sum_dz, b_ = sum_dzx;
+        a_ += __shfl_xor(a_, 16); a_ += __shfl_xor(a_, 32);
+        b_ += __shfl_xor(b_, 16); b_ += __shfl_xor(b_, 32);
+        if (q == 0) { Ss[wave_m * K::CN + cl] = a_; Ss[4 * K::CN + wave_m * K::CN + cl] = b_; }
         __syncthreads();
-        if (wave == 0 && q == 0) {
-#pragma unroll
-            for (int wn = 0; wn < K::WN; ++wn) {
-                const int c = 16 * wn + l16;
-                const float ta = (Ss[c] + Ss[K::CN + c]) + (Ss[2 * K::CN + c] + Ss[3 * K::CN + c]);
-                const float* Sb = Ss + 4 * K::CN;
-                const float tb = (Sb[c] + Sb[K::CN + c]) + (Sb[2 * K::CN + c] + Sb[3 * K::CN + c]);
-                *reinterpret_cast<float2*>(post.records + ((long)(n * BANDS + band) * C + co_base + c) * 2) = make_float2(ta, tb);
-            }
-        }
+        if (wave_m == 0 && q == 0)
+            *reinterpret_cast<float2*>(post.records + ((long)(n * BANDS + band) * C + co) * 2) =
+                make_float2(tile_total(Ss), tile_total(Ss + 4 * K::CN));
     }
 
     // ---- optional: batch-norm statistics of this workgroup's output tile, per channel:
     //      mean over its R*HW pixels and the sum of squared deviations from that mean
     //      (bn_partial[(g*C + c)*2 + {0,1}], g = image * bands + band), merged later like row slabs.
     if (bn_partial) {
-        float* Ss = lds + K::XS + K::WS;
         constexpr float inv_n = 1.0f / (float)(R * HW);
-        float mean_t[K::WN];
+        float mean_t = 0.f;
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
+            float s_ = 0.f;
 #pragma unroll
-            for (int wn = 0; wn < K::WN; ++wn) {
-                float s_ = 0.f;
+            for (int wm = 0; wm < K::WM; ++wm)
 #pragma unroll
-                for (int wm = 0; wm < K::WM; ++wm)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const float d = pass == 0 ? acc[wm][wn][v] : acc[wm][wn][v] - mean_t[wn];
-                        s_ += pass == 0 ? d : d * d;
-                    }
-                s_ += __shfl_xor(s_, 16);
-                s_ += __shfl_xor(s_, 32);
-                if (q == 0) Ss[wave * K::CN + 16 * wn + l16] = s_;
-            }
+                for (int v = 0; v < 4; ++v) {
+                    const float d = pass == 0 ? acc[wm][v] : acc[wm][v] - mean_t;
+                    s_ += pass == 0 ? d : d * d;
+                }
+            s_ += __shfl_xor(s_, 16);
+            s_ += __shfl_xor(s_, 32);
+            if (q == 0) Ss[wave_m * K::CN + cl] = s_;
             __syncthreads();
-#pragma unroll
-            for (int wn = 0; wn < K::WN; ++wn) {
-                const int c = 16 * wn + l16;
-                const float tot = (Ss[c] + Ss[K::CN + c]) + (Ss[2 * K::CN + c] + Ss[3 * K::CN + c]);
-                if (pass == 0) mean_t[wn] = tot * inv_n;
-                else if (wave == 0 && q == 0)
-                    *reinterpret_cast<float2*>(bn_partial + ((long)(n * BANDS + band) * C + co_base + c) * 2) = make_float2(mean_t[wn], tot);
-            }
+            const float tot = tile_total(Ss);
+            if (pass == 0) mean_t = tot * inv_n;
+            else if (wave_m == 0 && q == 0)
+                *reinterpret_cast<float2*>(bn_partial + ((long)(n * BANDS + band) * C + co) * 2) = make_float2(mean_t, tot);
             __syncthreads();
         }
     }
