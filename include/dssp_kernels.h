@@ -64,10 +64,34 @@ int dsspk_conv_bwd_data(void* stream, const float* dy_dev, const float* w_dev, c
 int dsspk_conv_bwd_data_post(void* stream, const float* dy_dev, const float* w_dev, const float* add_dev, float* dz_dev,
                              const float* mask_src_dev, const float* xc_dev, const float* stats_dev, float* records_dev,
                              int N, int H, int C);
+/* dsspk_conv_bwd_data_post with the batch norm that PRECEDES it in the backward direction folded into its loader:
+ * the convolution runs on
+ *   dx = gamma * invstd * (dz - totals[c] / M - xhat * totals[C + c] / M),  xhat = (xc - mean) * invstd,  M = N*H*H,
+ * computed from dz_dev (masked gradient at that batch norm's output), xc_dev (its input), stats_dev (its
+ * mean[C], invstd[C]), gamma_dev and totals_dev (sum dz [C], sum dz * xhat [C], see dsspk_bn_bwd_totals); dx is
+ * also stored to dx_dev for the d-filter convolution.  The epilogue is that of dsspk_conv_bwd_data_post
+ * (mask_src_dev, xc_post_dev, stats_post_dev, records_dev); out_dev may be add_dev itself (in place) but
+ * neither dz_dev nor dx_dev.  red_partial_dev != NULL: the kernel also carries the second stage of an earlier
+ * d-filter convolution, red_dw_dev[e] = sum over red_chunks of red_partial_dev[chunk][e], e < red_E (as extra
+ * workgroups, result identical to dsspk_wgrad_reduce). */
+int dsspk_conv_bwd_data_bn(void* stream, const float* dz_dev, const float* xc_dev, const float* stats_dev,
+                           const float* gamma_dev, const float* totals_dev, float* dx_dev, const float* w_dev,
+                           const float* add_dev, float* out_dev, const float* mask_src_dev, const float* xc_post_dev,
+                           const float* stats_post_dev, float* records_dev, const float* red_partial_dev,
+                           float* red_dw_dev, int red_E, int red_chunks, int N, int H, int C);
 /* dw[kh][kw][ci][co] = sum over batch and output pixels of x * dy.  Two stages (partial sums per
  * pixel chunk, then a fixed-order reduction).  scratch_dev: dsspk_conv_wgrad_scratch_floats(...) floats. */
 int dsspk_conv_bwd_weight(void* stream, const float* x_dev, const float* dy_dev, float* dw_dev, float* scratch_dev,
                           int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad);
+/* The two stages of dsspk_conv_bwd_weight on their own.  Stage 1 leaves *chunks_out (host memory) partial
+ * results of KH*KW*Cin*Cout floats each in scratch_dev; stage 2 sums them in a fixed order.  With records_dev
+ * != NULL stage 1 also carries, as extra workgroups, the sums dsspk_bn_bwd_totals computes (3x3 / stride 1 /
+ * Cin = Cout in {16, 32, 64} shapes only, -1 otherwise). */
+int dsspk_conv_bwd_weight_parts(void* stream, const float* x_dev, const float* dy_dev, float* scratch_dev,
+                                int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad,
+                                const float* records_dev, int G, int C, float* totals_dev, float* dgamma_dev,
+                                float* dbeta_dev, int* chunks_out);
+int dsspk_wgrad_reduce(void* stream, const float* partial_dev, float* dw_dev, int E, int chunks);
 size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad);
 
 /* dy[i] = a[i] > 0 ? dy[i] : 0 (in place). */
@@ -104,6 +128,11 @@ int dsspk_bn_bwd_reduce(void* stream, const float* x_dev, const float* stats_dev
 /* conv_parts > 0: scratch_dev holds that many (sum dz, sum dz*xhat) records written by dsspk_conv_bwd_data_post. */
 int dsspk_bn_bwd_dx(void* stream, const float* x_dev, const float* gamma_dev, const float* stats_dev, const float* dz_dev,
                     float* dx_dev, float* dgamma_dev, float* dbeta_dev, const float* scratch_dev, long M, int C, int conv_parts);
+/* Sums of G records of C channels, records_dev[(g * C + c) * 2 + {0, 1}] = (sum dz, sum dz * xhat) of one tile
+ * as written by dsspk_conv_bwd_data_post / _bn:  totals_dev[c] = dbeta_dev[c] = sum dz,
+ * totals_dev[C + c] = dgamma_dev[c] = sum dz * xhat.  C a multiple of 4; fixed summation order. */
+int dsspk_bn_bwd_totals(void* stream, const float* records_dev, int G, int C, float* totals_dev, float* dgamma_dev,
+                        float* dbeta_dev);
 size_t dsspk_bn_scratch_floats(long M, int C);
 
 /* dx[n][2ho][2wo][c] += dy[n][ho][wo][c] for c < C/2 (transpose of shortcut_mode 2). */

@@ -76,6 +76,10 @@ _SIGNATURES = {
     "dsspk_bn_bwd_reduce": (c_int, [c_void_p] * 6 + [c_long, c_int]),
     "dsspk_bn_bwd_dx": (c_int, [c_void_p] * 9 + [c_long, c_int, c_int]),
     "dsspk_conv_bwd_data_post": (c_int, [c_void_p] * 9 + [c_int] * 3),
+    "dsspk_conv_bwd_data_bn": (c_int, [c_void_p] * 16 + [c_int] * 5),
+    "dsspk_conv_bwd_weight_parts": (c_int, [c_void_p] * 4 + [c_int] * 9 + [c_void_p, c_int, c_int] + [c_void_p] * 4),
+    "dsspk_wgrad_reduce": (c_int, [c_void_p] * 3 + [c_int] * 2),
+    "dsspk_bn_bwd_totals": (c_int, [c_void_p, c_void_p, c_int, c_int] + [c_void_p] * 3),
     "dsspk_bn_scratch_floats": (c_size_t, [c_long, c_int]),
     "dsspk_shortcut_bwd_acc": (c_int, [c_void_p] * 3 + [c_int] * 4),
     "dsspk_gap_fwd": (c_int, [c_void_p] * 3 + [c_int] * 3),

@@ -11,6 +11,7 @@
 // gathered operand and the matching 16 x C slice of the filter in LDS (double buffered, next
 // slice prefetched into registers while the matrix cores work on the current one).
 #include "mma.hpp"
+#include "jobs.hpp"
 #include "../../include/dssp_kernels.h"
 
 // Specialised 3x3 / stride 1 / Cin = Cout kernels (k_conv3x3.hip); -2 = shape not covered.
@@ -23,7 +24,11 @@ int conv3x3_direct_prebn(hipStream_t s, const float* src, const float* records, 
                          const float* beta, float eps, const float* shortcut, float* act_out, float* stats_out,
                          const float* w, float* dst, float* bn_partial, int N, int HW, int C);
 int wgrad3x3_direct_parts(int N, int HW, int C);
-int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C);
+int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C, const jobs::TotalsJob& tj);
+int conv3x3_direct_dgrad_bn(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
+                            const float* totals, float* dx_out, const float* w, const float* add, float* out,
+                            const float* mask_src, const float* xc_post, const float* stats_post, float* records,
+                            const float* red_partial, float* red_dw, int red_E, int red_chunks, int N, int HW, int C);
 
 namespace {
 
@@ -300,7 +305,14 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
 // registers while the matrix cores work on the current one (two LDS buffers, one barrier per slice).
 template <int CI_T, int CO_T>
 __global__ __launch_bounds__(THREADS) void conv_wgrad_tile_kernel(const float* __restrict__ x, const float* __restrict__ dy,
-                                                                  float* __restrict__ partial, ConvGeom g, int stages) {
+                                                                  float* __restrict__ partial, ConvGeom g, int stages,
+                                                                  int own_x, jobs::TotalsJob tj) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    if ((int)blockIdx.x >= own_x) {                 // columns of workgroups behind the kernel's own carry the batch-norm sums job
+        const int jb = ((int)blockIdx.x - own_x) * gridDim.y + blockIdx.y;
+        if (jb < tj.blocks) jobs::bn_totals(tj, jb, lds);
+        return;
+    }
     constexpr int CIP = 16 * CI_T, COP = 16 * CO_T;
     constexpr int LDA = CIP + 4, LDB = COP + 4;
     constexpr int PIX = 64;
@@ -308,7 +320,6 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_tile_kernel(const float* _
     constexpr int TM = CI_T / WR, TN = CO_T / WC;                // tiles per wavefront
     static_assert(CI_T % WR == 0 && CO_T % WC == 0 && TM >= 1 && TN >= 1, "tile split");
     constexpr int XV = PIX * (CIP / 4) / THREADS, DV = PIX * (COP / 4) / THREADS;
-    extern __shared__ __attribute__((aligned(16))) float lds[];
     float* Xs = lds;                                   // [2][PIX * LDA]
     float* Ds = lds + 2 * PIX * LDA;                   // [2][PIX * LDB]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -382,8 +393,12 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_tile_kernel(const float* _
 }
 
 template <int CI_T, int CO_T>
-int launch_wgrad_tile(hipStream_t s, const float* x, const float* dy, float* scratch, const ConvGeom& g, int stages, dim3 grid) {
+int launch_wgrad_tile(hipStream_t s, const float* x, const float* dy, float* scratch, const ConvGeom& g, int stages, dim3 grid,
+                      const jobs::TotalsJob& tj) {
     constexpr size_t bytes = (size_t)2 * 64 * ((16 * CI_T + 4) + (16 * CO_T + 4)) * sizeof(float);
+    static_assert(bytes >= jobs::LDS_FLOATS * sizeof(float), "room for a carried job");
+    const int own_x = grid.x;
+    grid.x += (tj.blocks + grid.y - 1) / grid.y;
     static bool attr_set = false;
     auto kern = conv_wgrad_tile_kernel<CI_T, CO_T>;
     if (!attr_set) {
@@ -391,41 +406,27 @@ int launch_wgrad_tile(hipStream_t s, const float* x, const float* dy, float* scr
             return -1;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(THREADS), bytes, s, x, dy, scratch, g, stages);
+    hipLaunchKernelGGL(kern, grid, dim3(THREADS), bytes, s, x, dy, scratch, g, stages, own_x, tj);
     return DSSPK_LAUNCH_RC();
 }
 
-// d-filter, stage 2: dw[e] = sum over chunks of partial[chunk][e].  A workgroup owns 32 consecutive
-// elements (8 sixteen-byte columns) and splits the chunks over 32 row groups; every lane adds its
-// chunks in ascending order and the row groups are combined by a fixed tree.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dw,
-                                                           int E, int chunks) {
-    __shared__ float4 part[32][8];
-    const int cg = threadIdx.x & 7, rg = threadIdx.x >> 3;
-    const int e = (blockIdx.x * 8 + cg) * 4;
-    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (e < E)
-        for (int k = rg; k < chunks; k += 128) {
-            float4 v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                v[u] = (k + 32 * u < chunks) ? *reinterpret_cast<const float4*>(partial + (long)(k + 32 * u) * E + e)
-                                             : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
-        }
-    part[rg][cg] = s;
-    __syncthreads();
-    for (int h = 16; h >= 1; h >>= 1) {
-        if (rg < h) {
-            float4 a = part[rg][cg];
-            const float4 b = part[rg + h][cg];
-            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
-            part[rg][cg] = a;
-        }
-        __syncthreads();
-    }
-    if (rg == 0 && e < E) *reinterpret_cast<float4*>(dw + e) = part[0][cg];
+// d-filter, stage 2 as a kernel of its own: dw[e] = sum over chunks of partial[chunk][e] (jobs::wgrad_reduce).
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(jobs::ReduceJob j) {
+    __shared__ __attribute__((aligned(16))) float lds[jobs::LDS_FLOATS];
+    jobs::wgrad_reduce(j, blockIdx.x, lds);
+}
+
+// Batch-norm backward sums as a kernel of its own (jobs::bn_totals).
+__global__ __launch_bounds__(256) void bn_totals_kernel(jobs::TotalsJob j) {
+    __shared__ __attribute__((aligned(16))) float lds[jobs::LDS_FLOATS];
+    jobs::bn_totals(j, blockIdx.x, lds);
+}
+
+int launch_reduce(hipStream_t s, const float* partial, float* dw, int E, int chunks) {
+    jobs::ReduceJob j;
+    j.partial = partial; j.dw = dw; j.E = E; j.chunks = chunks; j.blocks = jobs::reduce_groups(E);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(j.blocks), dim3(256), 0, s, j);
+    return DSSPK_LAUNCH_RC();
 }
 
 bool geom(ConvGeom& g, int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
@@ -528,39 +529,36 @@ extern "C" size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, 
     return (size_t)chunks * KH * KW * Cin * Cout;
 }
 
-extern "C" int dsspk_conv_bwd_weight(void* stream, const float* x, const float* dy, float* dw, float* scratch,
-                                     int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
-    ConvGeom g;
-    if (!x || !dy || !dw || !scratch || !geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
+// Stage 1 of the d-filter convolution: partial[chunk][KH*KW*Cin*Cout] in scratch, *chunks_out chunks.
+// tj.blocks > 0 asks the kernel to carry the batch-norm sums job (only the direct 3x3 and the tile kernels can).
+static int wgrad_stage1(hipStream_t s, const float* x, const float* dy, float* scratch, const ConvGeom& g, int N, int H, int W,
+                        int Cin, int Cout, int KH, int KW, int stride, int pad, const jobs::TotalsJob& tj, int* chunks_out) {
     if (Cout != 16 && Cout != 32 && Cout != 64) return -1;
-    hipStream_t s = (hipStream_t)stream;
     const bool vec = Cin % 16 == 0;
     const int rows_total = KH * KW * Cin;
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
         const int parts = wgrad3x3_direct_parts(N, H, Cin);
         if (parts > 0) {
-            int rc = wgrad3x3_direct(s, x, dy, scratch, N, H, Cin);
-            if (rc) return rc;
-            const int E = rows_total * Cout;
-            hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(ceil_div(E, 32)), dim3(256), 0, s, scratch, dw, E, parts);
-            return DSSPK_LAUNCH_RC();
+            *chunks_out = parts;
+            return wgrad3x3_direct(s, x, dy, scratch, N, H, Cin, tj);
         }
     }
     const int gy = vec ? KH * KW : 1;
     const int stages = wgrad_stages(g, gy);
     const int chunks = ceil_div(g.M, 64L * stages);
+    *chunks_out = chunks;
     dim3 grid(chunks, gy);
 #define GO(CI, CO, V) hipLaunchKernelGGL((conv_wgrad_kernel<CI, CO, V>), grid, dim3(THREADS), 0, s, x, dy, scratch, g, stages, rows_total)
 #define GO_CO(CI, V) do { if (Cout == 16) GO(CI, 1, V); else if (Cout == 32) GO(CI, 2, V); else GO(CI, 4, V); } while (0)
     if (vec && (Cin / 16) * (Cout / 16) >= 4 && Cout >= 32 && (Cin == 16 || Cin == 32 || Cin == 64)) {
-        int rc2;
-        if (Cin == 64 && Cout == 64) rc2 = launch_wgrad_tile<4, 4>(s, x, dy, scratch, g, stages, grid);
-        else if (Cin == 32 && Cout == 64) rc2 = launch_wgrad_tile<2, 4>(s, x, dy, scratch, g, stages, grid);
-        else if (Cin == 32 && Cout == 32) rc2 = launch_wgrad_tile<2, 2>(s, x, dy, scratch, g, stages, grid);
-        else if (Cin == 64 && Cout == 32) rc2 = launch_wgrad_tile<4, 2>(s, x, dy, scratch, g, stages, grid);
-        else rc2 = launch_wgrad_tile<1, 4>(s, x, dy, scratch, g, stages, grid);
-        if (rc2) return rc2;
-    } else if (vec) {
+        if (Cin == 64 && Cout == 64) return launch_wgrad_tile<4, 4>(s, x, dy, scratch, g, stages, grid, tj);
+        if (Cin == 32 && Cout == 64) return launch_wgrad_tile<2, 4>(s, x, dy, scratch, g, stages, grid, tj);
+        if (Cin == 32 && Cout == 32) return launch_wgrad_tile<2, 2>(s, x, dy, scratch, g, stages, grid, tj);
+        if (Cin == 64 && Cout == 32) return launch_wgrad_tile<4, 2>(s, x, dy, scratch, g, stages, grid, tj);
+        return launch_wgrad_tile<1, 4>(s, x, dy, scratch, g, stages, grid, tj);
+    }
+    if (tj.blocks) return -1;
+    if (vec) {
         if (Cin == 16) GO_CO(1, true); else if (Cin == 32) GO_CO(2, true); else if (Cin == 64) GO_CO(4, true); else return -1;
     } else {
         const int tiles = ceil_div(rows_total, 16);
@@ -568,9 +566,59 @@ extern "C" int dsspk_conv_bwd_weight(void* stream, const float* x, const float* 
     }
 #undef GO_CO
 #undef GO
-    int rc = DSSPK_LAUNCH_RC();
-    if (rc) return rc;
-    const int E = rows_total * Cout;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(ceil_div(E, 32)), dim3(256), 0, s, scratch, dw, E, chunks);
     return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_conv_bwd_weight(void* stream, const float* x, const float* dy, float* dw, float* scratch,
+                                     int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
+    ConvGeom g;
+    if (!x || !dy || !dw || !scratch || !geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
+    int chunks = 0;
+    const int rc = wgrad_stage1((hipStream_t)stream, x, dy, scratch, g, N, H, W, Cin, Cout, KH, KW, stride, pad, jobs::TotalsJob(), &chunks);
+    if (rc) return rc;
+    return launch_reduce((hipStream_t)stream, scratch, dw, KH * KW * Cin * Cout, chunks);
+}
+
+static bool totals_job(jobs::TotalsJob& tj, const float* records, int G, int C, float* totals, float* dgamma, float* dbeta) {
+    tj = jobs::TotalsJob();
+    if (!records) return true;
+    if (!totals || !dgamma || !dbeta || G < 1 || C < 4 || C % 4) return false;
+    tj.records = records; tj.G = G; tj.C = C; tj.totals = totals; tj.dgamma = dgamma; tj.dbeta = dbeta; tj.blocks = C / 4;
+    return true;
+}
+
+extern "C" int dsspk_conv_bwd_weight_parts(void* stream, const float* x, const float* dy, float* scratch,
+                                           int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad,
+                                           const float* records, int G, int C, float* totals, float* dgamma, float* dbeta,
+                                           int* chunks_out) {
+    ConvGeom g;
+    jobs::TotalsJob tj;
+    if (!x || !dy || !scratch || !chunks_out || !geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
+    if (!totals_job(tj, records, G, C, totals, dgamma, dbeta)) return -1;
+    return wgrad_stage1((hipStream_t)stream, x, dy, scratch, g, N, H, W, Cin, Cout, KH, KW, stride, pad, tj, chunks_out);
+}
+
+extern "C" int dsspk_wgrad_reduce(void* stream, const float* partial, float* dw, int E, int chunks) {
+    if (!partial || !dw || E < 4 || E % 4 || chunks < 1) return -1;
+    return launch_reduce((hipStream_t)stream, partial, dw, E, chunks);
+}
+
+extern "C" int dsspk_bn_bwd_totals(void* stream, const float* records, int G, int C, float* totals, float* dgamma, float* dbeta) {
+    jobs::TotalsJob tj;
+    if (!records || !totals_job(tj, records, G, C, totals, dgamma, dbeta)) return -1;
+    hipLaunchKernelGGL(bn_totals_kernel, dim3(tj.blocks), dim3(256), 0, (hipStream_t)stream, tj);
+    return DSSPK_LAUNCH_RC();
+}
+
+extern "C" int dsspk_conv_bwd_data_bn(void* stream, const float* dz, const float* xc, const float* stats, const float* gamma,
+                                      const float* totals, float* dx, const float* w, const float* add, float* out,
+                                      const float* mask_src, const float* xc_post, const float* stats_post, float* records,
+                                      const float* red_partial, float* red_dw, int red_E, int red_chunks, int N, int H, int C) {
+    if (!dz || !xc || !stats || !gamma || !totals || !dx || !w || !out || !mask_src || !xc_post || !stats_post || !records || N < 1)
+        return -1;
+    if (out == dz || dx == dz || dx == out) return -1;
+    if (red_partial && (!red_dw || red_E < 4 || red_E % 4 || red_chunks < 1)) return -1;
+    const int rc = conv3x3_direct_dgrad_bn((hipStream_t)stream, dz, xc, stats, gamma, totals, dx, w, add, out, mask_src, xc_post,
+                                           stats_post, records, red_partial, red_dw, red_E, red_chunks, N, H, C);
+    return rc == -2 ? -1 : rc;
 }

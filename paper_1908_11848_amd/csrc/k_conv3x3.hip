@@ -17,6 +17,7 @@
 // taps reversed and its two channel indices swapped; only the filter fetch differs.
 #include "mma.hpp"
 #include "bn_merge.hpp"
+#include "jobs.hpp"
 #include "../../include/dssp_kernels.h"
 
 namespace {
@@ -69,12 +70,33 @@ struct PostBn {
     float* records;            // out: (sum dz, sum dz * xhat) per tile and channel
 };
 
+// Batch-norm backward applied to the input while it is loaded (PRE == 3, d-input convolutions): src is dz, the
+// masked gradient at the batch norm's output, and the convolution runs on
+//   dx = gamma * invstd * (dz - sum(dz) / M - xhat * sum(dz * xhat) / M),   xhat = (xc - mean) * invstd,
+// the gradient w.r.t. the batch norm's input xc; the workgroups also write dx (their own rows) for the
+// d-filter kernel.  The two sums come from the records of the epilogue that produced dz (TotalsJob).
+struct BwdBn {
+    const float* xc;           // the batch norm's input
+    const float* stats;        // its mean[C], invstd[C]
+    const float* gamma;
+    const float* totals;       // sum dz [C], sum dz * xhat [C]
+    float inv_m;               // 1 / (N * HW * HW)
+    float* dx_out;
+};
+
+// add and dst may be the same buffer (every element is read and written by the same lane); with PRE == 3
+// dst must differ from src, whose halo rows other workgroups still read.
 template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED, int PRE, bool POST = false>
 __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
-                                                          const float* __restrict__ add, float* __restrict__ dst,
-                                                          float* __restrict__ bn_partial, PreBn pre, PostBn post) {
+                                                          const float* add, float* dst,
+                                                          float* __restrict__ bn_partial, PreBn pre, PostBn post, BwdBn bwd,
+                                                          int conv_blocks, jobs::ReduceJob rj) {
     using K = Cfg<C, HW, R, NSPLIT>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
+    if ((int)blockIdx.x >= conv_blocks) {           // workgroups behind the convolution's own carry the reduction job
+        jobs::wgrad_reduce(rj, blockIdx.x - conv_blocks, lds);
+        return;
+    }
     float* Xs = lds;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, q = lane >> 4;
@@ -107,8 +129,9 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
     //      the statistics records (a latency chain of its own) then runs while they are in flight.
     constexpr int V = C / 4;
     constexpr int NL = ((R + 2) * K::TW * V + THREADS - 1) / THREADS;
-    float* Sh = lds + K::XS + K::SS + THREADS;       // mean[C], invstd[C] of the input (PRE)
-    float4 val[NL], scv[PRE == 2 ? NL : 1];
+    float* Sh = PRE == 3 ? lds + K::XS + K::SS                  // five per-channel vectors (PRE == 3)
+                         : lds + K::XS + K::SS + THREADS;       // mean[C], invstd[C] of the input (PRE == 1, 2)
+    float4 val[NL], scv[PRE >= 2 ? NL : 1];
 #pragma unroll
     for (int e = 0; e < NL; ++e) {
         const int idx = tid + e * THREADS;
@@ -120,10 +143,22 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
             const long off = (((long)n * HW + h) * HW + w) * C + 4 * v;
             val[e] = *reinterpret_cast<const float4*>(src + off);
             if constexpr (PRE == 2) scv[e] = *reinterpret_cast<const float4*>(pre.shortcut + off);
+            if constexpr (PRE == 3) scv[e] = *reinterpret_cast<const float4*>(bwd.xc + off);
         }
     }
-    if constexpr (PRE != 0) {           // mean / invstd of the input, merged from its records by records_merge_kernel
+    if constexpr (PRE == 1 || PRE == 2) {   // mean / invstd of the input, merged from its records by records_merge_kernel
         if (tid < 2 * C) Sh[tid] = pre.stats_out[tid];
+        __syncthreads();
+    }
+    if constexpr (PRE == 3) {               // mean, invstd, gamma * invstd, sum(dz) / M, sum(dz * xhat) / M
+        if (tid < C) {
+            const float is = bwd.stats[C + tid];
+            Sh[tid] = bwd.stats[tid];
+            Sh[C + tid] = is;
+            Sh[2 * C + tid] = bwd.gamma[tid] * is;
+            Sh[3 * C + tid] = bwd.totals[tid] * bwd.inv_m;
+            Sh[4 * C + tid] = bwd.totals[C + tid] * bwd.inv_m;
+        }
         __syncthreads();
     }
 #pragma unroll
@@ -133,7 +168,24 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
         const int pc = (idx / V) % K::TW, pr = idx / (V * K::TW);
         const int h = r_base + pr - 1, w = pc - 1;
         if (pr >= R + 2) continue;
-        if constexpr (PRE != 0) {
+        if constexpr (PRE == 3) {
+            if (h >= 0 && h < HW && w >= 0 && w < HW) {
+                const float4 mu = *reinterpret_cast<const float4*>(Sh + 4 * v);
+                const float4 is = *reinterpret_cast<const float4*>(Sh + C + 4 * v);
+                const float4 gi = *reinterpret_cast<const float4*>(Sh + 2 * C + 4 * v);
+                const float4 db = *reinterpret_cast<const float4*>(Sh + 3 * C + 4 * v);
+                const float4 dg = *reinterpret_cast<const float4*>(Sh + 4 * C + 4 * v);
+                float4 o;
+                o.x = gi.x * (val[e].x - db.x - (scv[e].x - mu.x) * is.x * dg.x);
+                o.y = gi.y * (val[e].y - db.y - (scv[e].y - mu.y) * is.y * dg.y);
+                o.z = gi.z * (val[e].z - db.z - (scv[e].z - mu.z) * is.z * dg.z);
+                o.w = gi.w * (val[e].w - db.w - (scv[e].w - mu.w) * is.w * dg.w);
+                val[e] = o;
+                if (split == 0 && pr >= 1 && pr <= R)
+                    *reinterpret_cast<float4*>(bwd.dx_out + (((long)n * HW + h) * HW + w) * C + 4 * v) = o;
+            }
+        }
+        if constexpr (PRE == 1 || PRE == 2) {
             if (h >= 0 && h < HW && w >= 0 && w < HW) {
                 const float4 mu = *reinterpret_cast<const float4*>(Sh + 4 * v);
                 const float4 is = *reinterpret_cast<const float4*>(Sh + C + 4 * v);
@@ -195,24 +247,33 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
         mu_c = post.stats[co];
         is_c = post.stats[C + co];
     }
+    // all loads of the epilogue first (dst may alias add, so the compiler cannot move them across the stores itself)
+    float addv[K::WM][4], maskv[POST ? K::WM : 1][4], xcv[POST ? K::WM : 1][4];
+    auto out_off = [&](int wm, int v) {
+        const int p = (wave_m * K::WM + wm) * 16 + 4 * q + v;
+        return (((long)n * HW + r_base + p / HW) * HW + p % HW) * C + co;
+    };
 #pragma unroll
-    for (int wm = 0; wm < K::WM; ++wm) {
-        const int run = wave_m * K::WM + wm;
+    for (int wm = 0; wm < K::WM; ++wm)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const int p = run * 16 + 4 * q + v;
-            const int h = r_base + p / HW, w = p % HW;
-            const long off = (((long)n * HW + h) * HW + w) * C + co;
-            float r = acc[wm][v] + (add ? add[off] : 0.f);
+            const long off = out_off(wm, v);
+            addv[wm][v] = add ? add[off] : 0.f;
+            if constexpr (POST) { maskv[wm][v] = post.mask_src[off]; xcv[wm][v] = post.xc[off]; }
+        }
+#pragma unroll
+    for (int wm = 0; wm < K::WM; ++wm)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float r = acc[wm][v] + addv[wm][v];
             if constexpr (POST) {
-                r = post.mask_src[off] > 0.f ? r : 0.f;
-                const float xh = (post.xc[off] - mu_c) * is_c;
+                r = maskv[wm][v] > 0.f ? r : 0.f;
+                const float xh = (xcv[wm][v] - mu_c) * is_c;
                 sum_dz += r;
                 sum_dzx = fmaf(r, xh, sum_dzx);
             }
-            dst[off] = r;
+            dst[out_off(wm, v)] = r;
         }
-    }
     // per-channel totals over the workgroup's tile: lanes of a wavefront by shuffles, then the WAVES_M
     // wavefronts that share the channel tile through LDS, in a fixed order
     float* Ss = lds + K::XS;
@@ -302,8 +363,10 @@ __global__ __launch_bounds__(THREADS) void records_merge_kernel(const float* __r
 
 template <int C, int HW, int R, int NSPLIT, bool T, int PRE = 0, bool POST = false>
 int launch(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial, int N,
-           const PreBn& pre = PreBn(), const PostBn& post = PostBn()) {
+           const PreBn& pre = PreBn(), const PostBn& post = PostBn(), const BwdBn& bwd = BwdBn(),
+           const jobs::ReduceJob& rj = jobs::ReduceJob()) {
     using K = Cfg<C, HW, R, NSPLIT>;
+    static_assert(K::LDS_BYTES >= jobs::LDS_FLOATS * sizeof(float), "room for a carried job");
     static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
     auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T, PRE, POST>;
     if (!attr_set) {
@@ -312,7 +375,9 @@ int launch(hipStream_t s, const float* src, const float* w, const float* add, fl
             return -1;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(N * (HW / R) * NSPLIT), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst, bn_partial, pre, post);
+    const int conv_blocks = N * (HW / R) * NSPLIT;
+    hipLaunchKernelGGL(kern, dim3(conv_blocks + rj.blocks), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst, bn_partial, pre, post,
+                       bwd, conv_blocks, rj);
     return DSSPK_LAUNCH_RC();
 }
 
@@ -369,6 +434,28 @@ int conv3x3_direct_dgrad_post(hipStream_t s, const float* dy, const float* w, co
     return -2;
 }
 
+// d-input convolution of dx = batch-norm backward of dz (see BwdBn), with the epilogue of conv3x3_direct_dgrad_post;
+// optionally carries the second stage of an earlier d-filter convolution (red_partial != NULL).
+int conv3x3_direct_dgrad_bn(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
+                            const float* totals, float* dx_out, const float* w, const float* add, float* out,
+                            const float* mask_src, const float* xc_post, const float* stats_post, float* records,
+                            const float* red_partial, float* red_dw, int red_E, int red_chunks, int N, int HW, int C) {
+    BwdBn bwd;
+    bwd.xc = xc; bwd.stats = stats; bwd.gamma = gamma; bwd.totals = totals; bwd.dx_out = dx_out;
+    bwd.inv_m = 1.0f / (float)((long)N * HW * HW);
+    PostBn post;
+    post.mask_src = mask_src; post.xc = xc_post; post.stats = stats_post; post.records = records;
+    jobs::ReduceJob rj = jobs::ReduceJob();
+    if (red_partial) {
+        rj.partial = red_partial; rj.dw = red_dw; rj.E = red_E; rj.chunks = red_chunks;
+        rj.blocks = jobs::reduce_groups(red_E) < 288 ? jobs::reduce_groups(red_E) : 288;
+    }
+    if (C == 16 && HW == 32) return launch<16, 32, 8, 1, true, 3, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj);
+    if (C == 32 && HW == 16) return launch<32, 16, 8, 1, true, 3, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj);
+    if (C == 64 && HW == 8) return launch<64, 8, 8, 2, true, 3, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj);
+    return -2;
+}
+
 // Number of per-workgroup statistics records (tiles of equal size) the forward kernel emits, 0 if the
 // shape is not covered by it.
 int conv3x3_direct_stat_parts(int N, int HW, int C) {
@@ -404,9 +491,13 @@ struct WCfg {
 
 template <int C, int HW, int R>
 __global__ __launch_bounds__(THREADS) void wgrad3x3_kernel(const float* __restrict__ x, const float* __restrict__ dy,
-                                                           float* __restrict__ partial) {
+                                                           float* __restrict__ partial, int own_blocks, jobs::TotalsJob tj) {
     using K = WCfg<C, HW, R>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
+    if ((int)blockIdx.x >= own_blocks) {            // workgroups behind the kernel's own carry the batch-norm sums job
+        jobs::bn_totals(tj, blockIdx.x - own_blocks, lds);
+        return;
+    }
     float* Xs = lds;
     float* Ds = lds + K::XS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -473,8 +564,9 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_kernel(const float* __restri
 }
 
 template <int C, int HW, int R>
-int launch_wgrad(hipStream_t s, const float* x, const float* dy, float* partial, int N) {
+int launch_wgrad(hipStream_t s, const float* x, const float* dy, float* partial, int N, const jobs::TotalsJob& tj) {
     using K = WCfg<C, HW, R>;
+    static_assert(K::LDS_BYTES >= jobs::LDS_FLOATS * sizeof(float), "room for a carried job");
     static bool attr_set = false;
     auto kern = wgrad3x3_kernel<C, HW, R>;
     if (!attr_set) {
@@ -483,7 +575,8 @@ int launch_wgrad(hipStream_t s, const float* x, const float* dy, float* partial,
             return -1;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(N * (HW / R)), dim3(THREADS), K::LDS_BYTES, s, x, dy, partial);
+    const int own = N * (HW / R);
+    hipLaunchKernelGGL(kern, dim3(own + tj.blocks), dim3(THREADS), K::LDS_BYTES, s, x, dy, partial, own, tj);
     return DSSPK_LAUNCH_RC();
 }
 
@@ -496,8 +589,8 @@ int wgrad3x3_direct_parts(int N, int HW, int C) {
     return 0;
 }
 
-int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C) {
-    if (C == 16 && HW == 32) return launch_wgrad<16, 32, 8>(s, x, dy, partial, N);
-    if (C == 32 && HW == 16) return launch_wgrad<32, 16, 8>(s, x, dy, partial, N);
+int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C, const jobs::TotalsJob& tj) {
+    if (C == 16 && HW == 32) return launch_wgrad<16, 32, 8>(s, x, dy, partial, N, tj);
+    if (C == 32 && HW == 16) return launch_wgrad<32, 16, 8>(s, x, dy, partial, N, tj);
     return -2;
 }

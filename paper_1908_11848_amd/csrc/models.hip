@@ -42,7 +42,7 @@ struct Plan {
     std::vector<Tens> tens;
 
     // common tail
-    size_t logits = 0, dlogits = 0, wg_scratch = 0, bn_scratch = 0, bn_scratch2 = 0;
+    size_t logits = 0, dlogits = 0, wg_scratch = 0, bn_scratch = 0, bn_scratch2 = 0, tot_a = 0, tot_b = 0;
     // MLP
     size_t mlp_a1 = 0, mlp_da1 = 0;
     // AlexNet-style
@@ -145,6 +145,7 @@ struct Plan {
         wg_scratch = a.floats(wg ? wg : 1);
         bn_scratch = a.floats(bn ? bn : 1);
         bn_scratch2 = a.floats(bn ? bn : 1);
+        tot_a = a.floats(128); tot_b = a.floats(128);          // batch-norm backward sums (2 x 64 channels at most)
         per_worker = a.off;
         return true;
     }
@@ -276,46 +277,96 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
     RUN(dsspk_gemm(s, F(P->dlogits), C, 1, w + P->fc_w, 1, C, F(P->dpooled), 64, m, 64, C, nullptr, 0));
     float *g0 = F(P->G[0]), *g1 = F(P->G[1]), *g2 = F(P->G[2]);     // g0: gradient w.r.t. the current block output
     RUN(dsspk_gap_bwd(s, F(P->dpooled), g0, m, 64, 64));
-    // Where a d-input convolution of the direct 3x3 kind produces the gradient of a post-ReLU activation, its
-    // epilogue also applies the ReLU mask and writes the sum records of the batch norm behind it, so that batch
-    // norm's backward pass starts at its dx kernel.  parts0 > 0: g0 already holds the masked dz of this block's
-    // BN2 and recB0 its records; 0: the stand-alone reduction kernel does both.
-    float* recB0 = F(P->bn_scratch2);
+    // Per convolution layer the backward pass is  BN backward -> d-input convolution -> d-filter convolution.
+    // Where the direct 3x3 kernels apply, and the gradient arrives already masked with sum records (written by the
+    // epilogue of the d-input convolution before it), these collapse into two launches:
+    //   d-input kernel : BN backward in its loader (stores dx for the d-filter kernel), ReLU mask + sum records of
+    //                    the next batch norm in its epilogue; carries the reduction of the PREVIOUS d-filter kernel
+    //   d-filter kernel: stage 1 only; carries the sums over the records the d-input kernel has just written
+    // Everything else (first and last layers, the stride-2 blocks) takes the stand-alone kernels.
+    //   parts0 > 0 : g0 holds the masked dz of this block's BN2 and recB0 its records
+    //   tot0       : their sums are in totB already (and dgamma / dbeta of BN2 stored)
+    //   pend       : a d-filter stage 1 whose reduction has not been launched yet (partial sums in scr)
+    float *recB0 = F(P->bn_scratch2), *totA = F(P->tot_a), *totB = F(P->tot_b);
     int parts0 = 0;
+    bool tot0 = false;
+    struct { float* dw; int E, chunks; bool on; } pend = {nullptr, 0, 0, false};
+    auto flush = [&]() -> int {
+        if (!pend.on) return 0;
+        pend.on = false;
+        return dsspk_wgrad_reduce(s, scr, pend.dw, pend.E, pend.chunks);
+    };
     for (int bi = (int)P->blocks.size() - 1; bi >= 0; --bi) {
         const ResBlock& B = P->blocks[bi];
         const float* xin = bi ? F(P->blocks[bi - 1].out) : F(P->stem_a);
         const int Ho = B.H / B.stride;
         const long M = (long)m * Ho * Ho;
-        // ---- BN2: g0 <- dz2 = g0 * [out > 0] (unless done already); g1 <- d conv2 output
-        if (!parts0) RUN(dsspk_bn_bwd_reduce(s, F(B.c2), F(B.st2), g0, F(B.out), recB0, M, B.cout));
-        RUN(dsspk_bn_bwd_dx(s, F(B.c2), w + B.g2, F(B.st2), g0, g1, g + B.g2, g + B.b2, recB0, M, B.cout, parts0));
-        RUN(dsspk_conv_bwd_weight(s, F(B.a1), g1, g + B.w2, scr, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));
-        // ---- conv2 d-input -> g2 = dz1 = d a1 * [a1 > 0], with BN1's sum records where the direct kernel applies
         const int parts1 = dsspk_conv_fwd_stat_parts(m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1);
-        if (parts1) {
-            RUN(dsspk_conv_bwd_data_post(s, g1, w + B.w2, nullptr, g2, F(B.a1), F(B.c1), F(B.st1), bscr, m, Ho, B.cout));
-        } else {
-            RUN(dsspk_conv_bwd_data(s, g1, w + B.w2, nullptr, g2, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));
-            RUN(dsspk_bn_bwd_reduce(s, F(B.c1), F(B.st1), g2, F(B.a1), bscr, M, B.cout));
-        }
-        RUN(dsspk_bn_bwd_dx(s, F(B.c1), w + B.g1, F(B.st1), g2, g1, g + B.g1, g + B.b1, bscr, M, B.cout, parts1));
-        RUN(dsspk_conv_bwd_weight(s, xin, g1, g + B.w1, scr, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1));
-        // ---- conv1 d-input (+ dz2 through an identity shortcut) -> g2 = gradient w.r.t. the block's input, which
-        //      is the previous block's (or the stem's) post-ReLU output: mask + records of ITS batch norm here too
         const bool identity = B.stride == 1 && B.cin == B.cout;
         const int partsp = identity ? dsspk_conv_fwd_stat_parts(m, B.H, B.H, B.cin, B.cout, 3, 3, 1, 1) : 0;
-        if (partsp) {
+        const bool fused1 = parts1 > 0 && partsp > 0;        // conv1's layer takes the two-launch form
+        bool tot1 = false;                                   // sums of BN1's records are in totA
+        int chunks = 0;
+        // ---- BN2 + conv2: g0 = dz2 -> g1 = d conv2 output, g2 = dz1 = d a1 * [a1 > 0] (+ BN1's records in bscr)
+        if (parts0 > 0 && parts1 > 0) {
+            if (!tot0) RUN(dsspk_bn_bwd_totals(s, recB0, parts0, B.cout, totB, g + B.g2, g + B.b2));
+            RUN(dsspk_conv_bwd_data_bn(s, g0, F(B.c2), F(B.st2), w + B.g2, totB, g1, w + B.w2, nullptr, g2,
+                                       F(B.a1), F(B.c1), F(B.st1), bscr, pend.on ? scr : nullptr, pend.dw, pend.E, pend.chunks,
+                                       m, Ho, B.cout));
+            pend.on = false;
+            RUN(dsspk_conv_bwd_weight_parts(s, F(B.a1), g1, scr, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1,
+                                            fused1 ? bscr : nullptr, parts1, B.cout, totA, g + B.g1, g + B.b1, &chunks));
+            pend = {g + B.w2, 9 * B.cout * B.cout, chunks, true};
+            tot1 = fused1;
+        } else {
+            RUN(flush());
+            if (!parts0) RUN(dsspk_bn_bwd_reduce(s, F(B.c2), F(B.st2), g0, F(B.out), recB0, M, B.cout));
+            RUN(dsspk_bn_bwd_dx(s, F(B.c2), w + B.g2, F(B.st2), g0, g1, g + B.g2, g + B.b2, recB0, M, B.cout, parts0));
+            RUN(dsspk_conv_bwd_weight(s, F(B.a1), g1, g + B.w2, scr, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));
+            if (parts1) {
+                RUN(dsspk_conv_bwd_data_post(s, g1, w + B.w2, nullptr, g2, F(B.a1), F(B.c1), F(B.st1), bscr, m, Ho, B.cout));
+            } else {
+                RUN(dsspk_conv_bwd_data(s, g1, w + B.w2, nullptr, g2, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1));
+                RUN(dsspk_bn_bwd_reduce(s, F(B.c1), F(B.st1), g2, F(B.a1), bscr, M, B.cout));
+            }
+        }
+        // ---- BN1 + conv1: g2 = dz1 -> g1 = d conv1 output; d-input (+ dz2 through an identity shortcut) = gradient
+        //      w.r.t. the block's input, which is the previous block's (or the stem's) post-ReLU output: mask +
+        //      records of ITS batch norm in the same kernel where the direct kernel applies
+        if (fused1) {
             const float* pc = bi ? F(P->blocks[bi - 1].c2) : F(P->stem_c);
             const float* pst = bi ? F(P->blocks[bi - 1].st2) : F(P->stem_st);
-            RUN(dsspk_conv_bwd_data_post(s, g1, w + B.w1, g0, g2, xin, pc, pst, recB0, m, B.H, B.cin));
+            if (!tot1) RUN(dsspk_bn_bwd_totals(s, bscr, parts1, B.cout, totA, g + B.g1, g + B.b1));
+            // output in place over the shortcut's gradient g0; g0 stays the gradient w.r.t. the previous block's output
+            RUN(dsspk_conv_bwd_data_bn(s, g2, F(B.c1), F(B.st1), w + B.g1, totA, g1, w + B.w1, g0, g0,
+                                       xin, pc, pst, recB0, pend.on ? scr : nullptr, pend.dw, pend.E, pend.chunks, m, B.H, B.cin));
+            pend.on = false;
+            const bool next_fused = bi > 0;                  // the previous block's conv2 has this convolution's shape
+            RUN(dsspk_conv_bwd_weight_parts(s, xin, g1, scr, m, B.H, B.H, B.cin, B.cout, 3, 3, 1, 1,
+                                            next_fused ? recB0 : nullptr, partsp, B.cin, totB,
+                                            next_fused ? g + P->blocks[bi - 1].g2 : nullptr, next_fused ? g + P->blocks[bi - 1].b2 : nullptr,
+                                            &chunks));
+            pend = {g + B.w1, 9 * B.cin * B.cout, chunks, true};
+            parts0 = partsp;
+            tot0 = next_fused;
         } else {
-            RUN(dsspk_conv_bwd_data(s, g1, w + B.w1, identity ? g0 : nullptr, g2, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1));
-            if (!identity) RUN(dsspk_shortcut_bwd_acc(s, g0, g2, m, Ho, Ho, B.cout));
+            RUN(flush());
+            RUN(dsspk_bn_bwd_dx(s, F(B.c1), w + B.g1, F(B.st1), g2, g1, g + B.g1, g + B.b1, bscr, M, B.cout, parts1));
+            RUN(dsspk_conv_bwd_weight(s, xin, g1, g + B.w1, scr, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1));
+            if (partsp) {
+                const float* pc = bi ? F(P->blocks[bi - 1].c2) : F(P->stem_c);
+                const float* pst = bi ? F(P->blocks[bi - 1].st2) : F(P->stem_st);
+                RUN(dsspk_conv_bwd_data_post(s, g1, w + B.w1, g0, g2, xin, pc, pst, recB0, m, B.H, B.cin));
+            } else {
+                RUN(dsspk_conv_bwd_data(s, g1, w + B.w1, identity ? g0 : nullptr, g2, m, B.H, B.H, B.cin, B.cout, 3, 3, B.stride, 1));
+                if (!identity) RUN(dsspk_shortcut_bwd_acc(s, g0, g2, m, Ho, Ho, B.cout));
+            }
+            parts0 = partsp;
+            tot0 = false;
+            float* t = g0; g0 = g2; g2 = t;
         }
-        parts0 = partsp;
-        float* t = g0; g0 = g2; g2 = t;
     }
+    RUN(flush());
     if (!parts0) RUN(dsspk_bn_bwd_reduce(s, F(P->stem_c), F(P->stem_st), g0, F(P->stem_a), recB0, (long)m * 1024, 16));
     RUN(dsspk_bn_bwd_dx(s, F(P->stem_c), w + P->stem_g, F(P->stem_st), g0, g1, g + P->stem_g, g + P->stem_b, recB0,
                         (long)m * 1024, 16, parts0));

@@ -218,6 +218,91 @@ def test_dgrad_with_relu_mask_and_batchnorm_records(oracle_nn, N, H, C, with_add
     assert rel_l2(host(dx), dxb) < 5e-6
 
 
+@pytest.mark.parametrize("N,H,C,with_add,carry", [(3, 32, 16, True, True), (5, 16, 32, False, True), (4, 8, 64, True, False),
+                                                  (128, 32, 16, True, True), (128, 8, 64, True, True)])
+def test_dgrad_with_batchnorm_backward_in_its_loader(oracle_nn, N, H, C, with_add, carry):
+    """dz -> [batch-norm backward folded into the loader] -> d-input convolution (+ add, in place) -> ReLU mask +
+    records of the next batch norm; the kernel optionally carries a d-filter reduction.  Against the oracle's
+    BN backward, d-input convolution and BN backward again."""
+    g = np.random.default_rng(N * 13 + H + C)
+    M = N * H * H
+    w = f32(g, (3, 3, C, C), (2.0 / (9 * C)) ** 0.5)
+    xa = f32(g, (N, H, H, C), 1.5) - np.float32(0.3)                    # input of batch norm A (behind the convolution)
+    xb = f32(g, (N, H, H, C), 2.0) + np.float32(0.5)                    # input of batch norm B (ahead of it)
+    ga, gb = (1 + 0.2 * g.standard_normal(C)).astype(np.float32), (1 + 0.2 * g.standard_normal(C)).astype(np.float32)
+    be = f32(g, C, 0.3)
+    dz = f32(g, (N, H, H, C)) * (g.random((N, H, H, C)) < 0.6)          # masked gradient at A's output
+    dz = dz.astype(np.float32)
+    add = f32(g, (N, H, H, C)) if with_add else None
+    L = B.lib()
+    st = stream_ptr()
+    parts = L.dsspk_conv_fwd_stat_parts(N, H, H, C, C, 3, 3, 1, 1)
+    XA, XB, GA, GB, BE, DZ, W = dev(xa), dev(xb), dev(ga), dev(gb), dev(be), dev(dz), dev(w)
+    tmp = empty((N, H, H, C)); actb = empty((N, H, H, C)); sta = empty(2 * C); stb = empty(2 * C)
+    scr = empty(L.dsspk_bn_scratch_floats(M, C))
+    rc(L.dsspk_bn_fwd(st, XA.data_ptr(), GA.data_ptr(), BE.data_ptr(), tmp.data_ptr(), sta.data_ptr(), scr.data_ptr(),
+                      M, C, 1e-5, 1, 0, None, 0, 0, 0, 0))
+    rc(L.dsspk_bn_fwd(st, XB.data_ptr(), GB.data_ptr(), BE.data_ptr(), actb.data_ptr(), stb.data_ptr(), scr.data_ptr(),
+                      M, C, 1e-5, 1, 0, None, 0, 0, 0, 0))
+    _, mean_a, invstd_a = oracle_nn.bn_fwd(xa.astype(np.float64), ga.astype(np.float64), be.astype(np.float64))
+    xhat = (xa.astype(np.float64) - mean_a) * invstd_a
+    tot = np.concatenate([dz.astype(np.float64).sum((0, 1, 2)), (dz * xhat).sum((0, 1, 2))]).astype(np.float32)
+    TOT = dev(tot)
+    E, chunks = 9 * C * C, 37
+    part = f32(g, (chunks, E))
+    PART = dev(part); red = empty(E)
+    dx = empty((N, H, H, C)); rec = empty(2 * parts * C)
+    out = dev(add) if with_add else empty((N, H, H, C))                 # in place over the add operand
+    rc(L.dsspk_conv_bwd_data_bn(st, DZ.data_ptr(), XA.data_ptr(), sta.data_ptr(), GA.data_ptr(), TOT.data_ptr(), dx.data_ptr(),
+                                W.data_ptr(), out.data_ptr() if with_add else None, out.data_ptr(),
+                                actb.data_ptr(), XB.data_ptr(), stb.data_ptr(), rec.data_ptr(),
+                                PART.data_ptr() if carry else None, red.data_ptr(), E, chunks, N, H, C))
+    dxo, _, _ = oracle_nn.bn_bwd(xa.astype(np.float64), ga.astype(np.float64), mean_a, invstd_a, dz.astype(np.float64))
+    assert rel_l2(host(dx), dxo) < 5e-6
+    r, _, _ = oracle_nn.conv2d_bwd(np.zeros((N, H, H, C)), w.astype(np.float64), dxo, 1, 1, False)
+    r = r + (add if with_add else 0)
+    dzo = np.where(host(actb) > 0, r, 0)
+    assert rel_l2(host(out), dzo) < 5e-6
+    if carry:
+        assert rel_l2(host(red), part.astype(np.float64).sum(0)) < TOL
+        ref = empty(E)
+        rc(L.dsspk_wgrad_reduce(st, PART.data_ptr(), ref.data_ptr(), E, chunks))
+        assert np.array_equal(host(red), host(ref))                     # same bits whoever carries the job
+    totb = empty(2 * C); dgam = empty(C); dbet = empty(C)
+    rc(L.dsspk_bn_bwd_totals(st, rec.data_ptr(), parts, C, totb.data_ptr(), dgam.data_ptr(), dbet.data_ptr()))
+    _, mean_b, invstd_b = oracle_nn.bn_fwd(xb.astype(np.float64), gb.astype(np.float64), be.astype(np.float64))
+    _, dgo, dbo = oracle_nn.bn_bwd(xb.astype(np.float64), gb.astype(np.float64), mean_b, invstd_b, dzo)
+    assert rel_l2(host(dgam), dgo) < 5e-6 and rel_l2(host(dbet), dbo) < 5e-6
+    assert np.array_equal(host(totb), np.concatenate([host(dbet), host(dgam)]))
+
+
+@pytest.mark.parametrize("N,H,C", [(3, 32, 16), (5, 16, 32), (4, 8, 64), (128, 16, 32), (128, 8, 64)])
+def test_wgrad_in_two_stages_carrying_batchnorm_sums(oracle_nn, N, H, C):
+    """Stage 1 of the d-filter convolution with the batch-norm sums job as extra workgroups, stage 2 on its own."""
+    g = np.random.default_rng(N * 17 + H + C)
+    x, dy = f32(g, (N, H, H, C)), f32(g, (N, H, H, C))
+    G = 4 * N if H == 32 else (2 * N if H == 16 else N)
+    rec = f32(g, (G, C, 2))
+    L = B.lib()
+    st = stream_ptr()
+    X, DY, REC = dev(x), dev(dy), dev(rec)
+    scr = empty(L.dsspk_conv_wgrad_scratch_floats(N, H, H, C, C, 3, 3, 1, 1))
+    tot = empty(2 * C); dgam = empty(C); dbet = empty(C); dw = empty((3, 3, C, C))
+    import ctypes
+    chunks = ctypes.c_int(0)
+    rc(L.dsspk_conv_bwd_weight_parts(st, X.data_ptr(), DY.data_ptr(), scr.data_ptr(), N, H, H, C, C, 3, 3, 1, 1,
+                                     REC.data_ptr(), G, C, tot.data_ptr(), dgam.data_ptr(), dbet.data_ptr(), ctypes.byref(chunks)))
+    assert chunks.value >= 1
+    rc(L.dsspk_wgrad_reduce(st, scr.data_ptr(), dw.data_ptr(), 9 * C * C, chunks.value))
+    _, dwo, _ = oracle_nn.conv2d_bwd(x.astype(np.float64), np.zeros((3, 3, C, C)), dy.astype(np.float64), 1, 1, False)
+    assert rel_l2(host(dw), dwo) < TOL
+    sums = rec.astype(np.float64).sum(0)
+    assert rel_l2(host(dbet), sums[:, 0]) < TOL and rel_l2(host(dgam), sums[:, 1]) < TOL
+    ref = empty(2 * C); d1 = empty(C); d2 = empty(C)
+    rc(L.dsspk_bn_bwd_totals(st, REC.data_ptr(), G, C, ref.data_ptr(), d1.data_ptr(), d2.data_ptr()))
+    assert np.array_equal(host(tot), host(ref)) and np.array_equal(host(tot), np.concatenate([host(dbet), host(dgam)]))
+
+
 # ------------------------------------------------------------------ elementwise / pooling
 @pytest.mark.parametrize("n", [5, 64, 100003])
 def test_relu_bwd_and_add(n):
