@@ -22,7 +22,7 @@ struct ReduceJob {
     float* dw;              // [E]
     int E;                  // multiple of 4
     int chunks;
-    int blocks;             // workgroups given to the job (0: none); each takes 32-element groups round-robin
+    int blocks;             // workgroups given to the job (0: none); each takes groups of elements round-robin
 };
 
 struct TotalsJob {
@@ -35,11 +35,32 @@ struct TotalsJob {
     int blocks;             // workgroups given to the job (0: none); must be C / 4
 };
 
-static inline int reduce_groups(int E) { return (E + 31) / 32; }
+// Two shapes, chosen by the number of chunks alone:
+//   many chunks (> 64): a workgroup owns 32 consecutive elements (8 sixteen-byte columns) at a time and splits
+//       the chunks over 32 row groups; every lane adds its chunks in ascending order and the row groups are
+//       combined by a tree.  One "group" = 32 elements.
+//   few chunks: a lane owns one sixteen-byte column and adds all chunks in ascending order, eight loads in
+//       flight at a time.  One "group" = 1024 elements.
+static inline bool reduce_by_rows(int chunks) { return chunks > 64; }
+static inline int reduce_groups(int E, int chunks) { return reduce_by_rows(chunks) ? (E + 31) / 32 : (E + 1023) / 1024; }
 
-// A workgroup owns 32 consecutive elements (8 sixteen-byte columns) at a time and splits the chunks over
-// 32 row groups; every lane adds its chunks in ascending order and the row groups are combined by a tree.
 __device__ __forceinline__ void wgrad_reduce(const ReduceJob& j, int block, float* lds) {
+    if (j.chunks <= 64) {
+        for (int e = (block * THREADS + (int)threadIdx.x) * 4; e < j.E; e += j.blocks * THREADS * 4) {
+            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int k0 = 0; k0 < j.chunks; k0 += 8) {
+                float4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)     // unconditional loads (index clamped), all in flight together
+                    v[u] = *reinterpret_cast<const float4*>(j.partial + (long)min(k0 + u, j.chunks - 1) * j.E + e);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (k0 + u < j.chunks) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+            }
+            *reinterpret_cast<float4*>(j.dw + e) = s;
+        }
+        return;
+    }
     float4(*part)[8] = reinterpret_cast<float4(*)[8]>(lds);
     const int cg = threadIdx.x & 7, rg = threadIdx.x >> 3;
     const int groups = (j.E + 31) / 32;

@@ -424,7 +424,7 @@ __global__ __launch_bounds__(256) void bn_totals_kernel(jobs::TotalsJob j) {
 
 int launch_reduce(hipStream_t s, const float* partial, float* dw, int E, int chunks) {
     jobs::ReduceJob j;
-    j.partial = partial; j.dw = dw; j.E = E; j.chunks = chunks; j.blocks = jobs::reduce_groups(E);
+    j.partial = partial; j.dw = dw; j.E = E; j.chunks = chunks; j.blocks = jobs::reduce_groups(E, chunks);
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(j.blocks), dim3(256), 0, s, j);
     return DSSPK_LAUNCH_RC();
 }

@@ -448,7 +448,8 @@ int conv3x3_direct_dgrad_bn(hipStream_t s, const float* dz, const float* xc, con
     jobs::ReduceJob rj = jobs::ReduceJob();
     if (red_partial) {
         rj.partial = red_partial; rj.dw = red_dw; rj.E = red_E; rj.chunks = red_chunks;
-        rj.blocks = jobs::reduce_groups(red_E) < 288 ? jobs::reduce_groups(red_E) : 288;
+        const int groups = jobs::reduce_groups(red_E, red_chunks);
+        rj.blocks = groups < 288 ? groups : 288;
     }
     if (C == 16 && HW == 32) return launch<16, 32, 8, 1, true, 3, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj);
     if (C == 32 && HW == 16) return launch<32, 16, 8, 1, true, 3, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj);
