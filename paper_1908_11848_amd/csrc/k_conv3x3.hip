@@ -109,22 +109,6 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
     const int co_base = split * K::CN;
     const int co = co_base + 16 * wave_n + l16;     // this lane's output channel (column of the MFMA tile)
 
-    // ---- filter values of this wavefront's 16 output channels, B[k][co] with k = 16 kc + 4 q + {0..3}:
-    //      forward : w[tap][k][co]           (four loads, C floats apart)
-    //      d-input : w[8 - tap][co][k]       (one 16-byte load, taps reversed)
-    float4 bf[9][K::KC];
-#pragma unroll
-    for (int tap = 0; tap < 9; ++tap)
-#pragma unroll
-        for (int kc = 0; kc < K::KC; ++kc) {
-            if constexpr (TRANSPOSED) {
-                bf[tap][kc] = *reinterpret_cast<const float4*>(wgt + ((long)(8 - tap) * C + co) * C + 16 * kc + 4 * q);
-            } else {
-                const float* wp = wgt + ((long)tap * C + 16 * kc + 4 * q) * C + co;
-                bf[tap][kc] = make_float4(wp[0], wp[C], wp[2 * C], wp[3 * C]);
-            }
-        }
-
     // ---- input halo tile, zero outside the image.  The raw loads are issued first; with PRE the merge of
     //      the statistics records (a latency chain of its own) then runs while they are in flight.
     constexpr int V = C / 4;
@@ -206,6 +190,21 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
         }
         *reinterpret_cast<float4*>(&Xs[(pr * K::TW + pc) * K::LDC + 4 * v]) = val[e];
     }
+    // ---- filter values of this wavefront's 16 output channels, B[k][co] with k = 16 kc + 4 q + {0..3}:
+    //      forward : w[tap][k][co]           (four loads, C floats apart)
+    //      d-input : w[8 - tap][co][k]       (one 16-byte load, taps reversed)
+    float4 bf[9][K::KC];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+        for (int kc = 0; kc < K::KC; ++kc) {
+            if constexpr (TRANSPOSED) {
+                bf[tap][kc] = *reinterpret_cast<const float4*>(wgt + ((long)(8 - tap) * C + co) * C + 16 * kc + 4 * q);
+            } else {
+                const float* wp = wgt + ((long)tap * C + 16 * kc + 4 * q) * C + co;
+                bf[tap][kc] = make_float4(wp[0], wp[C], wp[2 * C], wp[3 * C]);
+            }
+        }
     __syncthreads();
 
     // ---- 9 taps x C/16 k-chunks: A from LDS, B from registers
