@@ -563,6 +563,113 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_kernel(const float* __restri
     }
 }
 
+// The same for the last stage (64 channels, 8x8 images), where one image is only four pixel chunks and the
+// result is as large as 9 x 64 x 64: a workgroup owns 16 of the input channels (wavefront w: output channels
+// 16w..16w+15, all nine taps, 9 accumulator tiles) and IMGS whole images, one after the other; the next image's
+// x halo tile (its 16 channels only) and dy tile are fetched into registers while the matrix cores work on the
+// current one (two LDS buffers, one barrier per image).  Output: partial[image group][tap][ci][co], the
+// workgroup's 16 ci rows of it.
+template <int IMGS>
+__global__ __launch_bounds__(THREADS) void wgrad3x3_wide_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                                float* __restrict__ partial, int N, int own_blocks,
+                                                                jobs::TotalsJob tj) {
+    constexpr int C = 64, HW = 8, TW = HW + 2, CIW = 16, LDA = CIW + 4, LDB = C + 4;
+    constexpr int XS = TW * TW * LDA, DS = HW * HW * LDB, BUF = XS + DS;
+    constexpr int XV = (TW * TW * (CIW / 4) + THREADS - 1) / THREADS, DV = HW * HW * (C / 4) / THREADS;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    if ((int)blockIdx.x >= own_blocks) {
+        jobs::bn_totals(tj, blockIdx.x - own_blocks, lds);
+        return;
+    }
+    const int tid = threadIdx.x, lane = tid & 63, cot = tid >> 6;
+    const int l16 = lane & 15, q = lane >> 4;
+    const int cit = blockIdx.x % (C / CIW), grp = blockIdx.x / (C / CIW);
+    const int n0 = grp * IMGS;
+    const int nimg = min(IMGS, N - n0);
+    float4 rx[XV], rd[DV];
+    auto fetch = [&](int n) {
+#pragma unroll
+        for (int e = 0; e < XV; ++e) {
+            const int idx = tid + e * THREADS;
+            const int v = idx % (CIW / 4), pix = idx / (CIW / 4);
+            const int h = pix / TW - 1, w = pix % TW - 1;
+            rx[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (pix < TW * TW && h >= 0 && h < HW && w >= 0 && w < HW)
+                rx[e] = *reinterpret_cast<const float4*>(x + (((long)n * HW + h) * HW + w) * C + CIW * cit + 4 * v);
+        }
+#pragma unroll
+        for (int e = 0; e < DV; ++e) {
+            const int idx = tid + e * THREADS;
+            rd[e] = *reinterpret_cast<const float4*>(dy + (long)n * HW * HW * C + 4 * (long)idx);
+        }
+    };
+    auto stage = [&](int buf) {
+        float* Xs = lds + buf * BUF;
+        float* Ds = Xs + XS;
+#pragma unroll
+        for (int e = 0; e < XV; ++e) {
+            const int idx = tid + e * THREADS;
+            if (idx < TW * TW * (CIW / 4)) *reinterpret_cast<float4*>(&Xs[(idx / (CIW / 4)) * LDA + 4 * (idx % (CIW / 4))]) = rx[e];
+        }
+#pragma unroll
+        for (int e = 0; e < DV; ++e) {
+            const int idx = tid + e * THREADS;
+            *reinterpret_cast<float4*>(&Ds[(idx / (C / 4)) * LDB + 4 * (idx % (C / 4))]) = rd[e];
+        }
+    };
+    floatx4 acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    fetch(n0);
+    for (int i = 0; i < nimg; ++i) {
+        stage(i & 1);
+        __syncthreads();
+        if (i + 1 < nimg) fetch(n0 + i + 1);
+        const float* Xs = lds + (i & 1) * BUF;
+        const float* Ds = Xs + XS;
+#pragma unroll
+        for (int c = 0; c < HW * HW / 16; ++c) {
+            float b[4];
+            int xo[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int p = 16 * c + 4 * q + s;
+                b[s] = Ds[p * LDB + 16 * cot + l16];
+                xo[s] = ((p / HW) * TW + (p % HW)) * LDA + l16;
+            }
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const int toff = ((t / 3) * TW + (t % 3)) * LDA;
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Xs[xo[s] + toff], b[s], acc[t], 0, 0, 0);
+            }
+        }
+    }
+    mma::drain();
+    float* out = partial + (long)grp * 9 * C * C;
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) out[(t * C + CIW * cit + 4 * q + v) * C + 16 * cot + l16] = acc[t][v];
+}
+
+template <int IMGS>
+int launch_wgrad_wide(hipStream_t s, const float* x, const float* dy, float* partial, int N, const jobs::TotalsJob& tj) {
+    constexpr size_t bytes = (size_t)2 * (10 * 10 * 20 + 8 * 8 * 68) * sizeof(float);
+    static_assert(bytes >= jobs::LDS_FLOATS * sizeof(float), "room for a carried job");
+    static bool attr_set = false;
+    auto kern = wgrad3x3_wide_kernel<IMGS>;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+            return -1;
+        attr_set = true;
+    }
+    const int own = (N + IMGS - 1) / IMGS * 4;
+    hipLaunchKernelGGL(kern, dim3(own + tj.blocks), dim3(THREADS), bytes, s, x, dy, partial, N, own, tj);
+    return DSSPK_LAUNCH_RC();
+}
+
 template <int C, int HW, int R>
 int launch_wgrad(hipStream_t s, const float* x, const float* dy, float* partial, int N, const jobs::TotalsJob& tj) {
     using K = WCfg<C, HW, R>;
@@ -582,15 +689,19 @@ int launch_wgrad(hipStream_t s, const float* x, const float* dy, float* partial,
 
 }  // namespace
 
-// Number of partial results (workgroups) the specialised d-filter kernel writes, 0 if the shape is not covered.
+constexpr int WIDE_IMGS = 2;          // images per workgroup of the last stage's d-filter kernel
+
+// Number of partial results the specialised d-filter kernel writes, 0 if the shape is not covered.
 int wgrad3x3_direct_parts(int N, int HW, int C) {
     if (C == 16 && HW == 32) return N * 4;
     if (C == 32 && HW == 16) return N * 2;
+    if (C == 64 && HW == 8) return (N + WIDE_IMGS - 1) / WIDE_IMGS;
     return 0;
 }
 
 int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C, const jobs::TotalsJob& tj) {
     if (C == 16 && HW == 32) return launch_wgrad<16, 32, 8>(s, x, dy, partial, N, tj);
     if (C == 32 && HW == 16) return launch_wgrad<32, 16, 8>(s, x, dy, partial, N, tj);
+    if (C == 64 && HW == 8) return launch_wgrad_wide<WIDE_IMGS>(s, x, dy, partial, N, tj);
     return -2;
 }

@@ -276,7 +276,7 @@ def test_dgrad_with_batchnorm_backward_in_its_loader(oracle_nn, N, H, C, with_ad
     assert np.array_equal(host(totb), np.concatenate([host(dbet), host(dgam)]))
 
 
-@pytest.mark.parametrize("N,H,C", [(3, 32, 16), (5, 16, 32), (4, 8, 64), (128, 16, 32), (128, 8, 64)])
+@pytest.mark.parametrize("N,H,C", [(3, 32, 16), (5, 16, 32), (4, 8, 64), (7, 8, 64), (128, 16, 32), (128, 8, 64)])
 def test_wgrad_in_two_stages_carrying_batchnorm_sums(oracle_nn, N, H, C):
     """Stage 1 of the d-filter convolution with the batch-norm sums job as extra workgroups, stage 2 on its own."""
     g = np.random.default_rng(N * 17 + H + C)
