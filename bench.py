@@ -18,6 +18,9 @@ sys.path.insert(0, ROOT)
 
 import numpy as np  # noqa: E402
 
+WORKER_STREAMS = 0      # HIP streams the virtual workers are dealt onto; 0: one per worker (measured best: 279 vs
+                        # 249 pushes/s with 8 workers on 4 streams)
+
 
 def workload(name):
     """-> dict(model, config, K, s_L, r_max, lr, batch, n_classes, pool)"""
@@ -40,6 +43,7 @@ def main():
     ap.add_argument("--workload", default="resnet110")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--worker-streams", type=int, default=WORKER_STREAMS)
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         raise SystemExit("bench.py: this build emulates the K workers on ONE GPU; run it with --gpus 1 "
@@ -61,7 +65,8 @@ def main():
         segs = B.dssp_model_segments(B.model_id(wl["model"]), wl["n_classes"])
         w0 = inputs.init_weights(segs, wl["config"])
         xs, ys = inputs.batches(wl["config"], K, wl["pool"], wl["batch"], wl["n_classes"])
-        em = Emulation(wl["model"], K, wl["s_L"], wl["r_max"], wl["lr"], w0, wl["batch"], wl["n_classes"], xs, ys)
+        em = Emulation(wl["model"], K, wl["s_L"], wl["r_max"], wl["lr"], w0, wl["batch"], wl["n_classes"], xs, ys,
+                       worker_streams=a.worker_streams)
         n = int(w0.size)
     sched = em.schedule(d, log=False)
     sched.advance(a.warmup)
@@ -84,7 +89,8 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(1e3 * dt / a.steps, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s, batch %d, %d virtual workers, DSSP s_L=%d r_max=%d, %d params"
-                               % (wl["model"], wl["batch"], K, wl["s_L"], wl["r_max"], n)},
+                               % (wl["model"], wl["batch"], K, wl["s_L"], wl["r_max"], n),
+                   "worker_streams": min(K, a.worker_streams) if a.worker_streams else K},
         "weights_finite": finite,
     }
     if not a.no_roofline:

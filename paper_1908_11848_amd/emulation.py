@@ -13,10 +13,13 @@ from . import driver
 
 class Emulation:
     def __init__(self, model, K, s_L, r_max, lr, w0, batch=0, n_classes=0, xs=None, ys=None, grads=None,
-                 device="cuda:0"):
+                 device="cuda:0", worker_streams=None):
         """model: 'mlp' | 'alexnet_ds' | 'resnet<d>' | 'none'.
         w0: float32 initial weights.  xs[p][j] / ys[p][j]: pool of mini-batches of worker p
-        (cycled); grads[p]: fixed gradient buffers for model 'none' (server stress)."""
+        (cycled); grads[p]: fixed gradient buffers for model 'none' (server stress).
+        worker_streams: number of HIP streams the K workers are dealt onto (worker p -> stream p mod
+        that number; default one stream per worker).  Ordering between workers goes through the
+        library's events either way, so results do not depend on it."""
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required")
         B.lib()
@@ -35,7 +38,9 @@ class Emulation:
             for p in range(K):
                 self.grad[p].copy_(torch.from_numpy(np.ascontiguousarray(grads[p], dtype=np.float32)))
         self.loss = torch.zeros(K, dtype=torch.float32, device=self.dev)
-        self.streams = [torch.cuda.Stream(device=self.dev) for _ in range(K + 1)]
+        ns = K if not worker_streams else max(1, min(K, int(worker_streams)))
+        pool = [torch.cuda.Stream(device=self.dev) for _ in range(ns)]
+        self.streams = [pool[p % ns] for p in range(K)] + [torch.cuda.Stream(device=self.dev)]
         self.ctx = B.dssp_create(self.w, n, K, s_L, r_max, lr)
         B.dssp_set_stream(self.ctx, -1, self.streams[K])
         for p in range(K):

@@ -213,6 +213,11 @@ def test_resnet8_step_and_50_updates(oracle_nn):
     say("%s: weights after 50 updates %.2e, displacement %.2e" % (model, e, ed))
     assert e < WEIGHT_TOL
     em.close()
+    # several virtual workers per HIP stream (what the benchmark does with 8 workers): same schedule, same bits
+    em = Emulation(model, K, 3, 12, 0.05, w0, batch, 100, xs, ys, worker_streams=2)
+    log, _ = em.run(d, total=50)
+    assert log == out["log"] and np.array_equal(em.weights(), w_gpu)
+    em.close()
     em = Emulation(model, K, 3, 12, 0.05, w0, batch, 100, xs, ys)
     for p in range(K):
         B.dssp_pull(em.ctx, p, em.w_local[p])
