@@ -3,7 +3,8 @@
 Workload (default): ResNet-110 for CIFAR-shaped synthetic data, batch 128, 8 virtual workers on
 8 HIP streams, DSSP s_L = 3, r_max = 12, lr 0.05, heterogeneous seeded iteration times.
 One "step" = one push travelling the whole path: pull -> forward/backward -> push -> apply ->
-decision.  Prints one JSON line (see README for the fields).
+decision.  Prints one JSON line: metric, value (pushes/s), ms_per_step, config, roofline (dominant kernel),
+roofline_others, cpu_baseline (the CPU oracle on the first pushes of the same schedule).
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet110|alexnet_ds|mlp|stress]
 """
@@ -47,7 +48,7 @@ def main():
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         raise SystemExit("bench.py: this build emulates the K workers on ONE GPU; run it with --gpus 1 "
-                         "(no multi-GPU figure exists, see DESIGN.md on how the path would shard)")
+                         "(no multi-GPU figure exists)")
     import torch
     from paper_1908_11848_amd import binding as B, inputs
     from paper_1908_11848_amd.emulation import Emulation

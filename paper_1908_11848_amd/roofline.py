@@ -6,9 +6,9 @@ launchers.  `measure_*` time `reps` back-to-back launches on ONE stream with HIP
 on that same stream.  Run as a program it launches every case a few times and exits, which is
 what the hardware-counter passes are taken on:
 
-    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_fetch -o pmc \
+    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d out/pmc_fetch -o pmc \
         -- python3 -m paper_1908_11848_amd.roofline
-    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_write -o pmc \
+    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d out/pmc_write -o pmc \
         -- python3 -m paper_1908_11848_amd.roofline
 
 Algorithmic work per launch, with T = 4 * N * H * H * C bytes (one activation tensor of the stage) and
