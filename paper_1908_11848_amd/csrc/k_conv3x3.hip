@@ -38,6 +38,7 @@ struct Cfg {
     static constexpr int SS = 8 * CN;              // per-wavefront column sums (batch-norm records, two components)
     static constexpr int PS = THREADS + 2 * C;     // merge of the input's batch-norm records: tree + (mean, invstd)
     static constexpr size_t LDS_BYTES = (size_t)(XS + SS + PS) * sizeof(float);
+    static constexpr size_t LDS_BYTES_WG = LDS_BYTES + (size_t)XS * sizeof(float);   // + the x halo tile of the fused d-filter
     static_assert(WAVES_N == 1 || WAVES_N == 2 || WAVES_N == 4, "one 16-channel tile per wavefront");
     static_assert(RUNS % WAVES_M == 0 && WM >= 1, "band must give every wavefront at least one run");
 };
@@ -84,14 +85,26 @@ struct BwdBn {
     float* dx_out;
 };
 
+// Gradient w.r.t. the filter in the same kernel (WG, only with PRE == 3 and all channels in one workgroup): the
+// dx tile the loader has just built in LDS is the d-filter convolution's dy, so only the convolution's input x
+// (halo tile, a second LDS buffer) has to be fetched; dx itself never goes to memory.  After the d-input MFMA
+// loop the wavefronts accumulate, as wgrad3x3_kernel does, dw[tap][ci][co] += x[pixel + tap][ci] * dx[pixel][co]
+// over the band's pixels and store the workgroup's partial result; the sum over workgroups is a carried job of
+// a later kernel.
+struct WgradFused {
+    const float* x_in;         // input of the convolution (post-ReLU activation of the layer below)
+    float* partial;            // out: [workgroup][9][C][C]
+};
+
 // add and dst may be the same buffer (every element is read and written by the same lane); with PRE == 3
 // dst must differ from src, whose halo rows other workgroups still read.
-template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED, int PRE, bool POST = false>
+template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED, int PRE, bool POST = false, bool WG = false>
 __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
                                                           const float* add, float* dst,
                                                           float* __restrict__ bn_partial, PreBn pre, PostBn post, BwdBn bwd,
-                                                          int conv_blocks, jobs::ReduceJob rj) {
+                                                          int conv_blocks, jobs::ReduceJob rj, WgradFused wg) {
     using K = Cfg<C, HW, R, NSPLIT>;
+    static_assert(!WG || (PRE == 3 && NSPLIT == 1 && TRANSPOSED && (C == 16 || C == 32)), "fused d-filter: d-input form, whole channel range");
     extern __shared__ __attribute__((aligned(16))) float lds[];
     if ((int)blockIdx.x >= conv_blocks) {           // workgroups behind the convolution's own carry the reduction job
         jobs::wgrad_reduce(rj, blockIdx.x - conv_blocks, lds);
@@ -115,7 +128,8 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
     constexpr int NL = ((R + 2) * K::TW * V + THREADS - 1) / THREADS;
     float* Sh = PRE == 3 ? lds + K::XS + K::SS                  // five per-channel vectors (PRE == 3)
                          : lds + K::XS + K::SS + THREADS;       // mean[C], invstd[C] of the input (PRE == 1, 2)
-    float4 val[NL], scv[PRE >= 2 ? NL : 1];
+    float4 val[NL], scv[PRE >= 2 ? NL : 1], xin[WG ? NL : 1];
+    float* Xs2 = lds + K::XS + K::SS + K::PS;                   // x halo tile (WG)
 #pragma unroll
     for (int e = 0; e < NL; ++e) {
         const int idx = tid + e * THREADS;
@@ -128,6 +142,11 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
             val[e] = *reinterpret_cast<const float4*>(src + off);
             if constexpr (PRE == 2) scv[e] = *reinterpret_cast<const float4*>(pre.shortcut + off);
             if constexpr (PRE == 3) scv[e] = *reinterpret_cast<const float4*>(bwd.xc + off);
+        }
+        if constexpr (WG) {
+            xin[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (pr < R + 2 && h >= 0 && h < HW && w >= 0 && w < HW)
+                xin[e] = *reinterpret_cast<const float4*>(wg.x_in + (((long)n * HW + h) * HW + w) * C + 4 * v);
         }
     }
     if constexpr (PRE == 1 || PRE == 2) {   // mean / invstd of the input, merged from its records by records_merge_kernel
@@ -165,10 +184,11 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
                 o.z = gi.z * (val[e].z - db.z - (scv[e].z - mu.z) * is.z * dg.z);
                 o.w = gi.w * (val[e].w - db.w - (scv[e].w - mu.w) * is.w * dg.w);
                 val[e] = o;
-                if (split == 0 && pr >= 1 && pr <= R)
+                if (!WG && split == 0 && pr >= 1 && pr <= R)
                     *reinterpret_cast<float4*>(bwd.dx_out + (((long)n * HW + h) * HW + w) * C + 4 * v) = o;
             }
         }
+        if constexpr (WG) *reinterpret_cast<float4*>(&Xs2[(pr * K::TW + pc) * K::LDC + 4 * v]) = xin[e];
         if constexpr (PRE == 1 || PRE == 2) {
             if (h >= 0 && h < HW && w >= 0 && w < HW) {
                 const float4 mu = *reinterpret_cast<const float4*>(Sh + 4 * v);
@@ -260,6 +280,55 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
             addv[wm][v] = add ? add[off] : 0.f;
             if constexpr (POST) { maskv[wm][v] = post.mask_src[off]; xcv[wm][v] = post.xc[off]; }
         }
+    if constexpr (WG) {
+        // ---- d-filter of the same layer from the two LDS tiles, while the epilogue's operands are in flight:
+        //      A[ci][pixel] = x[pixel + tap][ci] (Xs2), B[pixel][co] = dx[pixel][co] (interior of Xs).
+        //      C = 16: one 16x16 tile per tap, the four wavefronts split the pixel chunks and are summed in a
+        //      fixed order; C = 32: wavefront w owns tile (w / 2, w % 2) and walks all chunks.
+        constexpr bool SPLIT_K = (C == 16);
+        constexpr int CHUNKS = R * HW / 16;
+        const int cit = SPLIT_K ? 0 : wave >> 1, cot = SPLIT_K ? 0 : wave & 1;
+        floatx4 dwa[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t) dwa[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int c = SPLIT_K ? wave : 0; c < CHUNKS; c += SPLIT_K ? 4 : 1) {
+            float b[4];
+            int xo[4];
+#pragma unroll
+            for (int s_ = 0; s_ < 4; ++s_) {
+                const int p = 16 * c + 4 * q + s_;
+                b[s_] = Xs[((p / HW + 1) * K::TW + (p % HW + 1)) * K::LDC + 16 * cot + l16];
+                xo[s_] = ((p / HW) * K::TW + (p % HW)) * K::LDC + 16 * cit + l16;
+            }
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const int toff = ((t / 3) * K::TW + (t % 3)) * K::LDC;
+#pragma unroll
+                for (int s_ = 0; s_ < 4; ++s_)
+                    dwa[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Xs2[xo[s_] + toff], b[s_], dwa[t], 0, 0, 0);
+            }
+        }
+        mma::drain();
+        float* pout = wg.partial + (long)blockIdx.x * 9 * C * C;
+        if constexpr (SPLIT_K) {
+            static_assert(!SPLIT_K || 4 * 9 * C * C <= 2 * K::XS + K::SS + K::PS, "room for the four partial sums");
+            __syncthreads();                              // both tiles are no longer needed: reuse LDS for the 4 partial sums
+            float* Red = lds;
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) Red[wave * 9 * C * C + (t * C + 4 * q + v) * C + l16] = dwa[t][v];
+            __syncthreads();
+            for (int idx = tid; idx < 9 * C * C; idx += THREADS)
+                pout[idx] = (Red[idx] + Red[9 * C * C + idx]) + (Red[2 * 9 * C * C + idx] + Red[3 * 9 * C * C + idx]);
+            __syncthreads();                              // before the epilogue's sums use LDS again
+        } else {
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) pout[(t * C + 16 * cit + 4 * q + v) * C + 16 * cot + l16] = dwa[t][v];
+        }
+    }
 #pragma unroll
     for (int wm = 0; wm < K::WM; ++wm)
 #pragma unroll
@@ -360,23 +429,24 @@ __global__ __launch_bounds__(THREADS) void records_merge_kernel(const float* __r
     }
 }
 
-template <int C, int HW, int R, int NSPLIT, bool T, int PRE = 0, bool POST = false>
+template <int C, int HW, int R, int NSPLIT, bool T, int PRE = 0, bool POST = false, bool WG = false>
 int launch(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial, int N,
            const PreBn& pre = PreBn(), const PostBn& post = PostBn(), const BwdBn& bwd = BwdBn(),
-           const jobs::ReduceJob& rj = jobs::ReduceJob()) {
+           const jobs::ReduceJob& rj = jobs::ReduceJob(), const WgradFused& wg = WgradFused()) {
     using K = Cfg<C, HW, R, NSPLIT>;
-    static_assert(K::LDS_BYTES >= jobs::LDS_FLOATS * sizeof(float), "room for a carried job");
+    constexpr size_t LDS_BYTES = WG ? K::LDS_BYTES_WG : K::LDS_BYTES;
+    static_assert(LDS_BYTES >= jobs::LDS_FLOATS * sizeof(float), "room for a carried job");
     static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
-    auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T, PRE, POST>;
+    auto kern = conv3x3_kernel<C, HW, R, NSPLIT, T, PRE, POST, WG>;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)K::LDS_BYTES) != hipSuccess)
+                                (int)LDS_BYTES) != hipSuccess)
             return -1;
         attr_set = true;
     }
     const int conv_blocks = N * (HW / R) * NSPLIT;
-    hipLaunchKernelGGL(kern, dim3(conv_blocks + rj.blocks), dim3(THREADS), K::LDS_BYTES, s, src, w, add, dst, bn_partial, pre, post,
-                       bwd, conv_blocks, rj);
+    hipLaunchKernelGGL(kern, dim3(conv_blocks + rj.blocks), dim3(THREADS), LDS_BYTES, s, src, w, add, dst, bn_partial, pre, post,
+                       bwd, conv_blocks, rj, wg);
     return DSSPK_LAUNCH_RC();
 }
 
@@ -453,6 +523,31 @@ int conv3x3_direct_dgrad_bn(hipStream_t s, const float* dz, const float* xc, con
     if (C == 16 && HW == 32) return launch<16, 32, 8, 1, true, 3, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj);
     if (C == 32 && HW == 16) return launch<32, 16, 8, 1, true, 3, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj);
     if (C == 64 && HW == 8) return launch<64, 8, 8, 2, true, 3, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj);
+    return -2;
+}
+
+// conv3x3_direct_dgrad_bn with the d-filter convolution of the same layer in the same kernel (see WgradFused);
+// dx is not stored.  Returns -2 for shapes the fused form does not cover (then the two-kernel form applies).
+int conv3x3_direct_dgrad_bn_wgrad(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
+                                  const float* totals, const float* w, const float* add, float* out,
+                                  const float* mask_src, const float* xc_post, const float* stats_post, float* records,
+                                  const float* x_in, float* partial, const float* red_partial, float* red_dw, int red_E,
+                                  int red_chunks, int N, int HW, int C) {
+    BwdBn bwd;
+    bwd.xc = xc; bwd.stats = stats; bwd.gamma = gamma; bwd.totals = totals; bwd.dx_out = nullptr;
+    bwd.inv_m = 1.0f / (float)((long)N * HW * HW);
+    PostBn post;
+    post.mask_src = mask_src; post.xc = xc_post; post.stats = stats_post; post.records = records;
+    jobs::ReduceJob rj = jobs::ReduceJob();
+    if (red_partial) {
+        rj.partial = red_partial; rj.dw = red_dw; rj.E = red_E; rj.chunks = red_chunks;
+        const int groups = jobs::reduce_groups(red_E, red_chunks);
+        rj.blocks = groups < 288 ? groups : 288;
+    }
+    WgradFused wg;
+    wg.x_in = x_in; wg.partial = partial;
+    if (C == 16 && HW == 32) return launch<16, 32, 8, 1, true, 3, true, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj, wg);
+    if (C == 32 && HW == 16) return launch<32, 16, 8, 1, true, 3, true, true>(s, dz, w, add, out, nullptr, N, PreBn(), post, bwd, rj, wg);
     return -2;
 }
 

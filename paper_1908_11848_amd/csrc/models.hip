@@ -42,7 +42,7 @@ struct Plan {
     std::vector<Tens> tens;
 
     // common tail
-    size_t logits = 0, dlogits = 0, wg_scratch = 0, bn_scratch = 0, bn_scratch2 = 0, tot_a = 0, tot_b = 0;
+    size_t logits = 0, dlogits = 0, wg_scratch = 0, wg_scratch2 = 0, bn_scratch = 0, bn_scratch2 = 0, tot_a = 0, tot_b = 0;
     // MLP
     size_t mlp_a1 = 0, mlp_da1 = 0;
     // AlexNet-style
@@ -143,6 +143,7 @@ struct Plan {
         dlogits = a.floats((size_t)m * classes);
         tens.push_back({2, logits, (int64_t)m * classes});
         wg_scratch = a.floats(wg ? wg : 1);
+        wg_scratch2 = a.floats(is_resnet(id) && wg ? wg : 1);   // d-filter partial sums alternate between the two
         bn_scratch = a.floats(bn ? bn : 1);
         bn_scratch2 = a.floats(bn ? bn : 1);
         tot_a = a.floats(128); tot_b = a.floats(128);          // batch-norm backward sums (2 x 64 channels at most)
@@ -279,22 +280,49 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
     RUN(dsspk_gap_bwd(s, F(P->dpooled), g0, m, 64, 64));
     // Per convolution layer the backward pass is  BN backward -> d-input convolution -> d-filter convolution.
     // Where the direct 3x3 kernels apply, and the gradient arrives already masked with sum records (written by the
-    // epilogue of the d-input convolution before it), these collapse into two launches:
-    //   d-input kernel : BN backward in its loader (stores dx for the d-filter kernel), ReLU mask + sum records of
-    //                    the next batch norm in its epilogue; carries the reduction of the PREVIOUS d-filter kernel
-    //   d-filter kernel: stage 1 only; carries the sums over the records the d-input kernel has just written
+    // epilogue of the d-input convolution before it), these collapse (regular_layer below):
+    //   stages 1-2: ONE kernel - BN backward in its loader, d-input convolution, ReLU mask + sum records of the
+    //               next batch norm in its epilogue, and the d-filter partial sums from the same LDS tiles (dx is
+    //               never stored) - followed by the small kernel that sums those records
+    //   stage 3   : the d-input kernel (stores dx), then the d-filter kernel, which carries the sums job
+    // In both forms the d-input kernel carries the reduction of the PREVIOUS layer's d-filter partial sums, which
+    // therefore alternate between two scratch buffers.
     // Everything else (first and last layers, the stride-2 blocks) takes the stand-alone kernels.
     //   parts0 > 0 : g0 holds the masked dz of this block's BN2 and recB0 its records
     //   tot0       : their sums are in totB already (and dgamma / dbeta of BN2 stored)
-    //   pend       : a d-filter stage 1 whose reduction has not been launched yet (partial sums in scr)
+    //   pend       : d-filter partial sums whose reduction has not been launched yet
     float *recB0 = F(P->bn_scratch2), *totA = F(P->tot_a), *totB = F(P->tot_b);
+    float* scrs[2] = {scr, F(P->wg_scratch2)};
     int parts0 = 0;
     bool tot0 = false;
-    struct { float* dw; int E, chunks; bool on; } pend = {nullptr, 0, 0, false};
+    struct { float* partial; float* dw; int E, chunks; bool on; } pend = {nullptr, nullptr, 0, 0, false};
     auto flush = [&]() -> int {
         if (!pend.on) return 0;
         pend.on = false;
-        return dsspk_wgrad_reduce(s, scr, pend.dw, pend.E, pend.chunks);
+        return dsspk_wgrad_reduce(s, pend.partial, pend.dw, pend.E, pend.chunks);
+    };
+    // dz (masked, records summed into tot) -> through BN (xc, st, gamma) -> dx -> d-input (+ add) with the mask / records
+    // epilogue (mask_src = x_in, xc_post, st_post -> records) into out, and d-filter (x_in, dx) into dw (pending).
+    // nrec != NULL: the records just written are summed into ntot / ndgamma / ndbeta for the next layer.
+    auto regular_layer = [&](const float* dz, const float* xc, const float* st, const float* gamma, const float* tot,
+                             const float* wt, const float* add, float* out, const float* x_in, const float* xc_post,
+                             const float* st_post, float* records, float* dw, int H, int Cc, bool sum_next, int nparts,
+                             float* ntot, float* ndgamma, float* ndbeta) -> int {
+        float* out_scr = (pend.on && pend.partial == scrs[0]) ? scrs[1] : scrs[0];
+        const float* rp = pend.on ? pend.partial : nullptr;
+        int chunks = dsspk_conv_bwd_fused_chunks(m, H, Cc);
+        if (chunks > 0) {
+            RUN(dsspk_conv_bwd_data_bn_wgrad(s, dz, xc, st, gamma, tot, wt, add, out, x_in, xc_post, st_post, records, x_in,
+                                             out_scr, rp, pend.dw, pend.E, pend.chunks, m, H, Cc));
+            if (sum_next) RUN(dsspk_bn_bwd_totals(s, records, nparts, Cc, ntot, ndgamma, ndbeta));
+        } else {
+            RUN(dsspk_conv_bwd_data_bn(s, dz, xc, st, gamma, tot, g1, wt, add, out, x_in, xc_post, st_post, records,
+                                       rp, pend.dw, pend.E, pend.chunks, m, H, Cc));
+            RUN(dsspk_conv_bwd_weight_parts(s, x_in, g1, out_scr, m, H, H, Cc, Cc, 3, 3, 1, 1, sum_next ? records : nullptr,
+                                            nparts, Cc, ntot, ndgamma, ndbeta, &chunks));
+        }
+        pend.partial = out_scr; pend.dw = dw; pend.E = 9 * Cc * Cc; pend.chunks = chunks; pend.on = true;
+        return 0;
     };
     for (int bi = (int)P->blocks.size() - 1; bi >= 0; --bi) {
         const ResBlock& B = P->blocks[bi];
@@ -306,17 +334,11 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
         const int partsp = identity ? dsspk_conv_fwd_stat_parts(m, B.H, B.H, B.cin, B.cout, 3, 3, 1, 1) : 0;
         const bool fused1 = parts1 > 0 && partsp > 0;        // conv1's layer takes the two-launch form
         bool tot1 = false;                                   // sums of BN1's records are in totA
-        int chunks = 0;
         // ---- BN2 + conv2: g0 = dz2 -> g1 = d conv2 output, g2 = dz1 = d a1 * [a1 > 0] (+ BN1's records in bscr)
         if (parts0 > 0 && parts1 > 0) {
             if (!tot0) RUN(dsspk_bn_bwd_totals(s, recB0, parts0, B.cout, totB, g + B.g2, g + B.b2));
-            RUN(dsspk_conv_bwd_data_bn(s, g0, F(B.c2), F(B.st2), w + B.g2, totB, g1, w + B.w2, nullptr, g2,
-                                       F(B.a1), F(B.c1), F(B.st1), bscr, pend.on ? scr : nullptr, pend.dw, pend.E, pend.chunks,
-                                       m, Ho, B.cout));
-            pend.on = false;
-            RUN(dsspk_conv_bwd_weight_parts(s, F(B.a1), g1, scr, m, Ho, Ho, B.cout, B.cout, 3, 3, 1, 1,
-                                            fused1 ? bscr : nullptr, parts1, B.cout, totA, g + B.g1, g + B.b1, &chunks));
-            pend = {g + B.w2, 9 * B.cout * B.cout, chunks, true};
+            RUN(regular_layer(g0, F(B.c2), F(B.st2), w + B.g2, totB, w + B.w2, nullptr, g2, F(B.a1), F(B.c1), F(B.st1), bscr,
+                              g + B.w2, Ho, B.cout, fused1, parts1, totA, g + B.g1, g + B.b1));
             tot1 = fused1;
         } else {
             RUN(flush());
@@ -338,15 +360,10 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
             const float* pst = bi ? F(P->blocks[bi - 1].st2) : F(P->stem_st);
             if (!tot1) RUN(dsspk_bn_bwd_totals(s, bscr, parts1, B.cout, totA, g + B.g1, g + B.b1));
             // output in place over the shortcut's gradient g0; g0 stays the gradient w.r.t. the previous block's output
-            RUN(dsspk_conv_bwd_data_bn(s, g2, F(B.c1), F(B.st1), w + B.g1, totA, g1, w + B.w1, g0, g0,
-                                       xin, pc, pst, recB0, pend.on ? scr : nullptr, pend.dw, pend.E, pend.chunks, m, B.H, B.cin));
-            pend.on = false;
             const bool next_fused = bi > 0;                  // the previous block's conv2 has this convolution's shape
-            RUN(dsspk_conv_bwd_weight_parts(s, xin, g1, scr, m, B.H, B.H, B.cin, B.cout, 3, 3, 1, 1,
-                                            next_fused ? recB0 : nullptr, partsp, B.cin, totB,
-                                            next_fused ? g + P->blocks[bi - 1].g2 : nullptr, next_fused ? g + P->blocks[bi - 1].b2 : nullptr,
-                                            &chunks));
-            pend = {g + B.w1, 9 * B.cin * B.cout, chunks, true};
+            RUN(regular_layer(g2, F(B.c1), F(B.st1), w + B.g1, totA, w + B.w1, g0, g0, xin, pc, pst, recB0, g + B.w1, B.H, B.cin,
+                              next_fused, partsp, totB, next_fused ? g + P->blocks[bi - 1].g2 : nullptr,
+                              next_fused ? g + P->blocks[bi - 1].b2 : nullptr));
             parts0 = partsp;
             tot0 = next_fused;
         } else {

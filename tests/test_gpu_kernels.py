@@ -276,6 +276,60 @@ def test_dgrad_with_batchnorm_backward_in_its_loader(oracle_nn, N, H, C, with_ad
     assert np.array_equal(host(totb), np.concatenate([host(dbet), host(dgam)]))
 
 
+@pytest.mark.parametrize("N,H,C,with_add", [(3, 32, 16, True), (5, 16, 32, False), (128, 32, 16, True), (128, 16, 32, True)])
+def test_dinput_and_dfilter_in_one_kernel(oracle_nn, N, H, C, with_add):
+    """The fused backward kernel of a regular layer: BN backward in the loader, d-input convolution with mask and
+    records, and the d-filter partial sums from the same LDS tiles; a reduction job of an earlier layer rides along."""
+    g = np.random.default_rng(N * 19 + H + C)
+    M = N * H * H
+    w = f32(g, (3, 3, C, C), (2.0 / (9 * C)) ** 0.5)
+    xa = f32(g, (N, H, H, C), 1.5) - np.float32(0.3)                    # input of batch norm A (behind the convolution)
+    xb = f32(g, (N, H, H, C), 2.0) + np.float32(0.5)                    # input of batch norm B (ahead of it)
+    ga, gb = (1 + 0.2 * g.standard_normal(C)).astype(np.float32), (1 + 0.2 * g.standard_normal(C)).astype(np.float32)
+    be = f32(g, C, 0.3)
+    dz = (f32(g, (N, H, H, C)) * (g.random((N, H, H, C)) < 0.6)).astype(np.float32)
+    add = f32(g, (N, H, H, C)) if with_add else None
+    L = B.lib()
+    st = stream_ptr()
+    parts = L.dsspk_conv_fwd_stat_parts(N, H, H, C, C, 3, 3, 1, 1)
+    chunks = L.dsspk_conv_bwd_fused_chunks(N, H, C)
+    assert chunks > 0
+    XA, XB, GA, GB, BE, DZ, W = dev(xa), dev(xb), dev(ga), dev(gb), dev(be), dev(dz), dev(w)
+    tmp = empty((N, H, H, C)); actb = empty((N, H, H, C)); sta = empty(2 * C); stb = empty(2 * C)
+    scr = empty(L.dsspk_bn_scratch_floats(M, C))
+    rc(L.dsspk_bn_fwd(st, XA.data_ptr(), GA.data_ptr(), BE.data_ptr(), tmp.data_ptr(), sta.data_ptr(), scr.data_ptr(),
+                      M, C, 1e-5, 1, 0, None, 0, 0, 0, 0))
+    rc(L.dsspk_bn_fwd(st, XB.data_ptr(), GB.data_ptr(), BE.data_ptr(), actb.data_ptr(), stb.data_ptr(), scr.data_ptr(),
+                      M, C, 1e-5, 1, 0, None, 0, 0, 0, 0))
+    _, mean_a, invstd_a = oracle_nn.bn_fwd(xa.astype(np.float64), ga.astype(np.float64), be.astype(np.float64))
+    xhat = (xa.astype(np.float64) - mean_a) * invstd_a
+    tot = np.concatenate([dz.astype(np.float64).sum((0, 1, 2)), (dz * xhat).sum((0, 1, 2))]).astype(np.float32)
+    TOT = dev(tot)
+    E, old_chunks = 9 * C * C, 19
+    part = f32(g, (old_chunks, E))
+    PART = dev(part); red = empty(E)
+    rec = empty(2 * parts * C); partial = empty(chunks * E); dw = empty((3, 3, C, C))
+    out = dev(add) if with_add else empty((N, H, H, C))                 # in place over the add operand
+    x_in = host(actb)                                                   # the convolution's input is B's post-ReLU output
+    rc(L.dsspk_conv_bwd_data_bn_wgrad(st, DZ.data_ptr(), XA.data_ptr(), sta.data_ptr(), GA.data_ptr(), TOT.data_ptr(),
+                                      W.data_ptr(), out.data_ptr() if with_add else None, out.data_ptr(),
+                                      actb.data_ptr(), XB.data_ptr(), stb.data_ptr(), rec.data_ptr(),
+                                      actb.data_ptr(), partial.data_ptr(), PART.data_ptr(), red.data_ptr(), E, old_chunks, N, H, C))
+    rc(L.dsspk_wgrad_reduce(st, partial.data_ptr(), dw.data_ptr(), E, chunks))
+    dxo, _, _ = oracle_nn.bn_bwd(xa.astype(np.float64), ga.astype(np.float64), mean_a, invstd_a, dz.astype(np.float64))
+    r, dwo, _ = oracle_nn.conv2d_bwd(x_in.astype(np.float64), w.astype(np.float64), dxo, 1, 1, False)
+    assert rel_l2(host(dw), dwo) < 5e-6
+    r = r + (add if with_add else 0)
+    dzo = np.where(host(actb) > 0, r, 0)
+    assert rel_l2(host(out), dzo) < 5e-6
+    assert rel_l2(host(red), part.astype(np.float64).sum(0)) < TOL
+    totb = empty(2 * C); dgam = empty(C); dbet = empty(C)
+    rc(L.dsspk_bn_bwd_totals(st, rec.data_ptr(), parts, C, totb.data_ptr(), dgam.data_ptr(), dbet.data_ptr()))
+    _, mean_b, invstd_b = oracle_nn.bn_fwd(xb.astype(np.float64), gb.astype(np.float64), be.astype(np.float64))
+    _, dgo, dbo = oracle_nn.bn_bwd(xb.astype(np.float64), gb.astype(np.float64), mean_b, invstd_b, dzo)
+    assert rel_l2(host(dgam), dgo) < 5e-6 and rel_l2(host(dbet), dbo) < 5e-6
+
+
 @pytest.mark.parametrize("N,H,C", [(3, 32, 16), (5, 16, 32), (4, 8, 64), (7, 8, 64), (128, 16, 32), (128, 8, 64)])
 def test_wgrad_in_two_stages_carrying_batchnorm_sums(oracle_nn, N, H, C):
     """Stage 1 of the d-filter convolution with the batch-norm sums job as extra workgroups, stage 2 on its own."""
