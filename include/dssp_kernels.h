@@ -80,13 +80,14 @@ int dsspk_conv_bwd_data_bn(void* stream, const float* dz_dev, const float* xc_de
                            const float* stats_post_dev, float* records_dev, const float* red_partial_dev,
                            float* red_dw_dev, int red_E, int red_chunks, int N, int H, int C);
 /* dsspk_conv_bwd_data_bn and stage 1 of the d-filter convolution of the same layer in ONE kernel: dx is used from
- * LDS for both and never stored.  x_in_dev: the convolution's input [N][H][H][C]; partial_dev receives
+ * LDS for both and never stored.  x_in_dev: the convolution's input [N][H][H][C], a post-ReLU activation, which is
+ * also the source of the epilogue's ReLU mask (there is no separate mask_src_dev); partial_dev receives
  * dsspk_conv_bwd_fused_chunks(N, H, C) partial results of 9*C*C floats (to be summed by dsspk_wgrad_reduce or a
  * later call's red_* job; must not be the buffer red_partial_dev points to).  Only where
  * dsspk_conv_bwd_fused_chunks(...) > 0 (C = 16 at 32x32, C = 32 at 16x16), -1 otherwise. */
 int dsspk_conv_bwd_data_bn_wgrad(void* stream, const float* dz_dev, const float* xc_dev, const float* stats_dev,
                                  const float* gamma_dev, const float* totals_dev, const float* w_dev,
-                                 const float* add_dev, float* out_dev, const float* mask_src_dev,
+                                 const float* add_dev, float* out_dev,
                                  const float* xc_post_dev, const float* stats_post_dev, float* records_dev,
                                  const float* x_in_dev, float* partial_dev, const float* red_partial_dev,
                                  float* red_dw_dev, int red_E, int red_chunks, int N, int H, int C);

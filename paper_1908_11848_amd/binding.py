@@ -77,7 +77,7 @@ _SIGNATURES = {
     "dsspk_bn_bwd_dx": (c_int, [c_void_p] * 9 + [c_long, c_int, c_int]),
     "dsspk_conv_bwd_data_post": (c_int, [c_void_p] * 9 + [c_int] * 3),
     "dsspk_conv_bwd_data_bn": (c_int, [c_void_p] * 16 + [c_int] * 5),
-    "dsspk_conv_bwd_data_bn_wgrad": (c_int, [c_void_p] * 17 + [c_int] * 5),
+    "dsspk_conv_bwd_data_bn_wgrad": (c_int, [c_void_p] * 16 + [c_int] * 5),
     "dsspk_conv_bwd_fused_chunks": (c_int, [c_int] * 3),
     "dsspk_conv_bwd_weight_parts": (c_int, [c_void_p] * 4 + [c_int] * 9 + [c_void_p, c_int, c_int] + [c_void_p] * 4),
     "dsspk_wgrad_reduce": (c_int, [c_void_p] * 3 + [c_int] * 2),

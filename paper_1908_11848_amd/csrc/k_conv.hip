@@ -31,7 +31,7 @@ int conv3x3_direct_dgrad_bn(hipStream_t s, const float* dz, const float* xc, con
                             const float* red_partial, float* red_dw, int red_E, int red_chunks, int N, int HW, int C);
 int conv3x3_direct_dgrad_bn_wgrad(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
                                   const float* totals, const float* w, const float* add, float* out,
-                                  const float* mask_src, const float* xc_post, const float* stats_post, float* records,
+                                  const float* xc_post, const float* stats_post, float* records,
                                   const float* x_in, float* partial, const float* red_partial, float* red_dw, int red_E,
                                   int red_chunks, int N, int HW, int C);
 
@@ -635,16 +635,16 @@ extern "C" int dsspk_conv_bwd_fused_chunks(int N, int H, int C) {
 
 extern "C" int dsspk_conv_bwd_data_bn_wgrad(void* stream, const float* dz, const float* xc, const float* stats, const float* gamma,
                                             const float* totals, const float* w, const float* add, float* out,
-                                            const float* mask_src, const float* xc_post, const float* stats_post, float* records,
+                                            const float* xc_post, const float* stats_post, float* records,
                                             const float* x_in, float* partial, const float* red_partial, float* red_dw,
                                             int red_E, int red_chunks, int N, int H, int C) {
-    if (!dz || !xc || !stats || !gamma || !totals || !w || !out || !mask_src || !xc_post || !stats_post || !records || !x_in ||
+    if (!dz || !xc || !stats || !gamma || !totals || !w || !out || !xc_post || !stats_post || !records || !x_in ||
         !partial || N < 1)
         return -1;
     if (out == dz || partial == red_partial) return -1;
     if (red_partial && (!red_dw || red_E < 4 || red_E % 4 || red_chunks < 1)) return -1;
     if (dsspk_conv_bwd_fused_chunks(N, H, C) == 0) return -1;
-    const int rc = conv3x3_direct_dgrad_bn_wgrad((hipStream_t)stream, dz, xc, stats, gamma, totals, w, add, out, mask_src, xc_post,
+    const int rc = conv3x3_direct_dgrad_bn_wgrad((hipStream_t)stream, dz, xc, stats, gamma, totals, w, add, out, xc_post,
                                                  stats_post, records, x_in, partial, red_partial, red_dw, red_E, red_chunks, N, H, C);
     return rc == -2 ? -1 : rc;
 }

@@ -92,7 +92,8 @@ struct BwdBn {
 // over the band's pixels and store the workgroup's partial result; the sum over workgroups is a carried job of
 // a later kernel.
 struct WgradFused {
-    const float* x_in;         // input of the convolution (post-ReLU activation of the layer below)
+    const float* x_in;         // input of the convolution (post-ReLU activation of the layer below); it is also the
+                               // source of the epilogue's ReLU mask, which is then taken from the LDS tile
     float* partial;            // out: [workgroup][9][C][C]
 };
 
@@ -278,7 +279,15 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
         for (int v = 0; v < 4; ++v) {
             const long off = out_off(wm, v);
             addv[wm][v] = add ? add[off] : 0.f;
-            if constexpr (POST) { maskv[wm][v] = post.mask_src[off]; xcv[wm][v] = post.xc[off]; }
+            if constexpr (POST) {
+                if constexpr (WG) {     // the mask source is the convolution's input, whose tile is in LDS
+                    const int p = (wave_m * K::WM + wm) * 16 + 4 * q + v;
+                    maskv[wm][v] = Xs2[((p / HW + 1) * K::TW + (p % HW + 1)) * K::LDC + co];
+                } else {
+                    maskv[wm][v] = post.mask_src[off];
+                }
+                xcv[wm][v] = post.xc[off];
+            }
         }
     if constexpr (WG) {
         // ---- d-filter of the same layer from the two LDS tiles, while the epilogue's operands are in flight:
@@ -530,14 +539,14 @@ int conv3x3_direct_dgrad_bn(hipStream_t s, const float* dz, const float* xc, con
 // dx is not stored.  Returns -2 for shapes the fused form does not cover (then the two-kernel form applies).
 int conv3x3_direct_dgrad_bn_wgrad(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
                                   const float* totals, const float* w, const float* add, float* out,
-                                  const float* mask_src, const float* xc_post, const float* stats_post, float* records,
+                                  const float* xc_post, const float* stats_post, float* records,
                                   const float* x_in, float* partial, const float* red_partial, float* red_dw, int red_E,
                                   int red_chunks, int N, int HW, int C) {
     BwdBn bwd;
     bwd.xc = xc; bwd.stats = stats; bwd.gamma = gamma; bwd.totals = totals; bwd.dx_out = nullptr;
     bwd.inv_m = 1.0f / (float)((long)N * HW * HW);
     PostBn post;
-    post.mask_src = mask_src; post.xc = xc_post; post.stats = stats_post; post.records = records;
+    post.mask_src = x_in; post.xc = xc_post; post.stats = stats_post; post.records = records;
     jobs::ReduceJob rj = jobs::ReduceJob();
     if (red_partial) {
         rj.partial = red_partial; rj.dw = red_dw; rj.E = red_E; rj.chunks = red_chunks;

@@ -312,7 +312,7 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
         const float* rp = pend.on ? pend.partial : nullptr;
         int chunks = dsspk_conv_bwd_fused_chunks(m, H, Cc);
         if (chunks > 0) {
-            RUN(dsspk_conv_bwd_data_bn_wgrad(s, dz, xc, st, gamma, tot, wt, add, out, x_in, xc_post, st_post, records, x_in,
+            RUN(dsspk_conv_bwd_data_bn_wgrad(s, dz, xc, st, gamma, tot, wt, add, out, xc_post, st_post, records, x_in,
                                              out_scr, rp, pend.dw, pend.E, pend.chunks, m, H, Cc));
             if (sum_next) RUN(dsspk_bn_bwd_totals(s, records, nparts, Cc, ntot, ndgamma, ndbeta));
         } else {

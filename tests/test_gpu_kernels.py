@@ -313,7 +313,7 @@ def test_dinput_and_dfilter_in_one_kernel(oracle_nn, N, H, C, with_add):
     x_in = host(actb)                                                   # the convolution's input is B's post-ReLU output
     rc(L.dsspk_conv_bwd_data_bn_wgrad(st, DZ.data_ptr(), XA.data_ptr(), sta.data_ptr(), GA.data_ptr(), TOT.data_ptr(),
                                       W.data_ptr(), out.data_ptr() if with_add else None, out.data_ptr(),
-                                      actb.data_ptr(), XB.data_ptr(), stb.data_ptr(), rec.data_ptr(),
+                                      XB.data_ptr(), stb.data_ptr(), rec.data_ptr(),
                                       actb.data_ptr(), partial.data_ptr(), PART.data_ptr(), red.data_ptr(), E, old_chunks, N, H, C))
     rc(L.dsspk_wgrad_reduce(st, partial.data_ptr(), dw.data_ptr(), E, chunks))
     dxo, _, _ = oracle_nn.bn_bwd(xa.astype(np.float64), ga.astype(np.float64), mean_a, invstd_a, dz.astype(np.float64))
