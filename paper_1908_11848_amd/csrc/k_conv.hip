@@ -446,7 +446,9 @@ bool geom(ConvGeom& g, int N, int H, int W, int Cin, int Cout, int KH, int KW, i
 }
 
 int wgrad_stages(const ConvGeom& g, int grid_y) {
-    long s = g.M * grid_y / (64L * 288L);
+    // about 288 workgroups; four times as many where the gather is scalar (Cin not a multiple of 16: the loads of a
+    // slice are many and narrow, so more of them have to be in flight)
+    long s = g.M * grid_y / (64L * (g.IC % 16 ? 1152L : 288L));
     if (s < 1) s = 1;
     if (s > 16) s = 16;
     return (int)s;

@@ -350,7 +350,15 @@ __global__ __launch_bounds__(THREADS) void gap_fwd_kernel(const float* __restric
     if (i >= N * C) return;
     const int n = i / C, c = i % C;
     float s = 0.f;
-    for (int k = 0; k < HW; ++k) s += x[((long)n * HW + k) * C + c];
+    int k = 0;
+    for (; k + 8 <= HW; k += 8) {            // eight loads in flight, added in pixel order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = x[((long)n * HW + k + u) * C + c];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; k < HW; ++k) s += x[((long)n * HW + k) * C + c];
     y[i] = s / (float)HW;
 }
 
@@ -365,27 +373,33 @@ __global__ __launch_bounds__(THREADS) void gap_bwd_kernel(const float* __restric
 }
 
 // ------------------------------------------------------------------ softmax cross-entropy
-// One thread per sample; the batch mean of the loss is summed by thread 0 in index order.
+// One wavefront per sample at a time (lanes stride over the classes, so rows are read coalesced); maxima and sums
+// are combined across the lanes by a fixed butterfly; the batch mean of the loss is summed by thread 0 in index order.
 __global__ void softmax_xent_kernel(const float* __restrict__ z, const int32_t* __restrict__ label,
                                     float* __restrict__ dz, float* __restrict__ loss, int m, int C) {
     extern __shared__ float row_loss[];
-    const int i = threadIdx.x;
-    if (i < m) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const float invm = 1.0f / (float)m;
+    for (int i = wave; i < m; i += nwaves) {
         const float* zi = z + (long)i * C;
-        float mx = zi[0];
-        for (int j = 1; j < C; ++j) mx = fmaxf(mx, zi[j]);
+        float mx = -INFINITY;
+        for (int j = lane; j < C; j += 64) mx = fmaxf(mx, zi[j]);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
         float se = 0.f;
-        for (int j = 0; j < C; ++j) se += expf(zi[j] - mx);
+        for (int j = lane; j < C; j += 64) se += expf(zi[j] - mx);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) se += __shfl_xor(se, o);
         const int y = label[i];
-        row_loss[i] = logf(se) + mx - zi[y];
-        const float inv = 1.0f / se, invm = 1.0f / (float)m;
-        for (int j = 0; j < C; ++j) dz[(long)i * C + j] = (expf(zi[j] - mx) * inv - (j == y ? 1.f : 0.f)) * invm;
+        if (lane == 0) row_loss[i] = logf(se) + mx - zi[y];
+        const float inv = 1.0f / se;
+        for (int j = lane; j < C; j += 64) dz[(long)i * C + j] = (expf(zi[j] - mx) * inv - (j == y ? 1.f : 0.f)) * invm;
     }
     __syncthreads();
-    if (i == 0 && loss) {
+    if (threadIdx.x == 0 && loss) {
         float s = 0.f;
         for (int k = 0; k < m; ++k) s += row_loss[k];
-        *loss = s / (float)m;
+        *loss = s * invm;
     }
 }
 
@@ -515,7 +529,7 @@ extern "C" int dsspk_gap_bwd(void* stream, const float* dy, float* dx, int N, in
 
 extern "C" int dsspk_softmax_xent(void* stream, const float* z, const int32_t* y, float* dz, float* loss, int m, int C) {
     if (!z || !y || !dz || m < 1 || m > 1024 || C < 1 || C > 1024) return -1;
-    const int threads = (m + 63) / 64 * 64;
+    const int threads = m >= 16 ? 1024 : 64 * m;          // one wavefront per sample, at most 16 at a time
     hipLaunchKernelGGL(softmax_xent_kernel, dim3(1), dim3(threads), sizeof(float) * m, (hipStream_t)stream, z, y, dz, loss, m, C);
     return DSSPK_LAUNCH_RC();
 }
