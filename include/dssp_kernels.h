@@ -28,8 +28,10 @@ int dsspk_pull(void* stream, float* dst_dev, const float* w_dev, int64_t n,
  * leading dimension ldc.  bias_dev may be NULL. */
 int dsspk_gemm(void* stream, const float* A_dev, long a_rs, long a_cs, const float* B_dev, long b_rs, long b_cs,
                float* C_dev, long ldc, int M, int N, int K, const float* bias_dev, int relu);
-/* out[j] = sum_i X[i][j], X is [M][N] row-major.  Fixed summation order. */
-int dsspk_colsum(void* stream, const float* X_dev, float* out_dev, long M, int N);
+/* out[j] = sum_i X[i][j], X is [M][N] row-major.  Fixed summation order (row slabs, then the slabs). */
+int dsspk_colsum(void* stream, const float* X_dev, float* out_dev, float* scratch_dev, long M, int N);
+/* Floats of scratch_dev dsspk_colsum needs for an [M][N] matrix (0 for short matrices: scratch_dev may be NULL). */
+size_t dsspk_colsum_scratch_floats(long M, int N);
 
 /* Convolution (cross-correlation, zero padding), implicit GEMM on fp32 MFMA.
  * Ho = (H + 2*pad - KH)/stride + 1.  bias_dev may be NULL; relu applies max(.,0) to the output.

@@ -73,18 +73,34 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(const float* __restrict__
         }
 }
 
-// out[j] = sum_i X[i][j]: one workgroup per 64 columns, 4 row groups, fixed order.
-__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ X, float* __restrict__ out, long M, int N) {
+// out[slab][j] = sum over the rows i of the slab of X[i][j]: a workgroup owns 64 columns and one slab of rows
+// (blockIdx.y), four row lanes each adding every fourth row of the slab in ascending order, eight loads in flight.
+// Tall matrices take two passes (slab sums into scratch, then the sum of the slabs), short ones a single slab.
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ X, float* __restrict__ out, long M, int N,
+                                                     long rows_per_slab) {
     __shared__ float part[4][64];
     const int c = threadIdx.x & 63, g = threadIdx.x >> 6;
     const int col = blockIdx.x * 64 + c;
+    const long r0 = (long)blockIdx.y * rows_per_slab;
+    const long r1 = r0 + rows_per_slab < M ? r0 + rows_per_slab : M;
     float s = 0.f;
-    if (col < N)
-        for (long i = g; i < M; i += 4) s += X[i * N + col];
+    if (col < N) {
+        long i = r0 + g;
+        for (; i + 28 < r1; i += 32) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = X[(i + 4 * u) * N + col];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; i < r1; i += 4) s += X[i * N + col];
+    }
     part[g][c] = s;
     __syncthreads();
-    if (g == 0 && col < N) out[col] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
+    if (g == 0 && col < N) out[(long)blockIdx.y * N + col] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
 }
+
+constexpr int COLSUM_SLABS = 256;
 
 }  // namespace
 
@@ -103,8 +119,21 @@ extern "C" int dsspk_gemm(void* stream, const float* A, long a_rs, long a_cs, co
     return DSSPK_LAUNCH_RC();
 }
 
-extern "C" int dsspk_colsum(void* stream, const float* X, float* out, long M, int N) {
+extern "C" size_t dsspk_colsum_scratch_floats(long M, int N) {
+    return M > 1024 && N >= 1 ? (size_t)COLSUM_SLABS * N : 0;
+}
+
+extern "C" int dsspk_colsum(void* stream, const float* X, float* out, float* scratch, long M, int N) {
     if (!X || !out || M < 1 || N < 1) return -1;
-    hipLaunchKernelGGL(colsum_kernel, dim3(ceil_div(N, 64)), dim3(256), 0, (hipStream_t)stream, X, out, M, N);
+    hipStream_t s = (hipStream_t)stream;
+    if (dsspk_colsum_scratch_floats(M, N) == 0) {
+        hipLaunchKernelGGL(colsum_kernel, dim3(ceil_div(N, 64), 1), dim3(256), 0, s, X, out, M, N, M);
+        return DSSPK_LAUNCH_RC();
+    }
+    if (!scratch) return -1;
+    const long rps = (M + COLSUM_SLABS - 1) / COLSUM_SLABS;
+    const int slabs = ceil_div(M, rps);
+    hipLaunchKernelGGL(colsum_kernel, dim3(ceil_div(N, 64), slabs), dim3(256), 0, s, X, scratch, M, N, rps);
+    hipLaunchKernelGGL(colsum_kernel, dim3(ceil_div(N, 64), 1), dim3(256), 0, s, scratch, out, (long)slabs, N, (long)slabs);
     return DSSPK_LAUNCH_RC();
 }

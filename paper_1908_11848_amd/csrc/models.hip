@@ -42,7 +42,7 @@ struct Plan {
     std::vector<Tens> tens;
 
     // common tail
-    size_t logits = 0, dlogits = 0, wg_scratch = 0, wg_scratch2 = 0, bn_scratch = 0, bn_scratch2 = 0, tot_a = 0, tot_b = 0;
+    size_t logits = 0, dlogits = 0, colsum_scratch = 0, wg_scratch = 0, wg_scratch2 = 0, bn_scratch = 0, bn_scratch2 = 0, tot_a = 0, tot_b = 0;
     // MLP
     size_t mlp_a1 = 0, mlp_da1 = 0;
     // AlexNet-style
@@ -142,6 +142,7 @@ struct Plan {
         logits = a.floats((size_t)m * classes);
         dlogits = a.floats((size_t)m * classes);
         tens.push_back({2, logits, (int64_t)m * classes});
+        colsum_scratch = a.floats(id == DSSP_MODEL_ALEXNET_DS ? dsspk_colsum_scratch_floats((long)m * 32 * 32, 64) + 1 : 1);
         wg_scratch = a.floats(wg ? wg : 1);
         wg_scratch2 = a.floats(is_resnet(id) && wg ? wg : 1);   // d-filter partial sums alternate between the two
         bn_scratch = a.floats(bn ? bn : 1);
@@ -169,11 +170,11 @@ int step_mlp(Plan* P, char* ws, void* s, const float* x, const int32_t* y, const
     RUN(dsspk_gemm(s, a1, 256, 1, w + w2, C, 1, z, C, m, C, 256, w + b2, 0));
     RUN(dsspk_softmax_xent(s, z, y, dz, loss, m, C));
     RUN(dsspk_gemm(s, a1, 1, 256, dz, C, 1, g + w2, C, 256, C, m, nullptr, 0));          // dW2 = a1^T dz
-    RUN(dsspk_colsum(s, dz, g + b2, m, C));
+    RUN(dsspk_colsum(s, dz, g + b2, nullptr, m, C));
     RUN(dsspk_gemm(s, dz, C, 1, w + w2, 1, C, da1, 256, m, 256, C, nullptr, 0));         // da1 = dz W2^T
     RUN(dsspk_relu_bwd(s, da1, a1, (long)m * 256));
     RUN(dsspk_gemm(s, x, 1, 3072, da1, 256, 1, g + w1, 256, 3072, 256, m, nullptr, 0));  // dW1 = x^T dz1
-    RUN(dsspk_colsum(s, da1, g + b1, m, 256));
+    RUN(dsspk_colsum(s, da1, g + b1, nullptr, m, 256));
     return 0;
 }
 
@@ -197,25 +198,25 @@ int step_alexnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, c
     RUN(dsspk_softmax_xent(s, z, y, dz, loss, m, C));
     // backward
     RUN(dsspk_gemm(s, a4, 1, 192, dz, C, 1, g + fw3, C, 192, C, m, nullptr, 0));
-    RUN(dsspk_colsum(s, dz, g + fb3, m, C));
+    RUN(dsspk_colsum(s, dz, g + fb3, nullptr, m, C));
     RUN(dsspk_gemm(s, dz, C, 1, w + fw3, 1, C, da4, 192, m, 192, C, nullptr, 0));
     RUN(dsspk_relu_bwd(s, da4, a4, (long)m * 192));
     RUN(dsspk_gemm(s, a3, 1, 384, da4, 192, 1, g + fw2, 192, 384, 192, m, nullptr, 0));
-    RUN(dsspk_colsum(s, da4, g + fb2, m, 192));
+    RUN(dsspk_colsum(s, da4, g + fb2, nullptr, m, 192));
     RUN(dsspk_gemm(s, da4, 192, 1, w + fw2, 1, 192, da3, 384, m, 384, 192, nullptr, 0));
     RUN(dsspk_relu_bwd(s, da3, a3, (long)m * 384));
     RUN(dsspk_gemm(s, p2, 1, 3136, da3, 384, 1, g + fw1, 384, 3136, 384, m, nullptr, 0));
-    RUN(dsspk_colsum(s, da3, g + fb1, m, 384));
+    RUN(dsspk_colsum(s, da3, g + fb1, nullptr, m, 384));
     RUN(dsspk_gemm(s, da3, 384, 1, w + fw1, 1, 384, dp2, 3136, m, 3136, 384, nullptr, 0));
     RUN(dsspk_maxpool_bwd(s, dp2, arg2, da2, m, 15, 15, 64));
     RUN(dsspk_relu_bwd(s, da2, a2, (long)m * 15 * 15 * 64));
     RUN(dsspk_conv_bwd_weight(s, p1, da2, g + cw2, scr, m, 15, 15, 64, 64, 5, 5, 1, 2));
-    RUN(dsspk_colsum(s, da2, g + cb2, (long)m * 15 * 15, 64));
+    RUN(dsspk_colsum(s, da2, g + cb2, F(P->colsum_scratch), (long)m * 15 * 15, 64));
     RUN(dsspk_conv_bwd_data(s, da2, w + cw2, nullptr, dp1, m, 15, 15, 64, 64, 5, 5, 1, 2));
     RUN(dsspk_maxpool_bwd(s, dp1, arg1, da1, m, 32, 32, 64));
     RUN(dsspk_relu_bwd(s, da1, a1, (long)m * 32 * 32 * 64));
     RUN(dsspk_conv_bwd_weight(s, x, da1, g + cw1, scr, m, 32, 32, 3, 64, 5, 5, 1, 2));
-    RUN(dsspk_colsum(s, da1, g + cb1, (long)m * 32 * 32, 64));
+    RUN(dsspk_colsum(s, da1, g + cb1, F(P->colsum_scratch), (long)m * 32 * 32, 64));
     return 0;
 }
 
@@ -274,7 +275,7 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
     RUN(dsspk_softmax_xent(s, F(P->logits), y, F(P->dlogits), loss, m, C));
     // ---- backward
     RUN(dsspk_gemm(s, F(P->pooled), 1, 64, F(P->dlogits), C, 1, g + P->fc_w, C, 64, C, m, nullptr, 0));
-    RUN(dsspk_colsum(s, F(P->dlogits), g + P->fc_b, m, C));
+    RUN(dsspk_colsum(s, F(P->dlogits), g + P->fc_b, nullptr, m, C));
     RUN(dsspk_gemm(s, F(P->dlogits), C, 1, w + P->fc_w, 1, C, F(P->dpooled), 64, m, 64, C, nullptr, 0));
     float *g0 = F(P->G[0]), *g1 = F(P->G[1]), *g2 = F(P->G[2]);     // g0: gradient w.r.t. the current block output
     RUN(dsspk_gap_bwd(s, F(P->dpooled), g0, m, 64, 64));

@@ -210,6 +210,22 @@ def measure_all(dev, stream, n_params):
     return out
 
 
+def _alexnet_conv2_case(dev):
+    """Forward of the AlexNet-style network's second convolution (5x5, 64 -> 64 at 15x15, bias + ReLU), its largest layer."""
+    import torch
+    from . import binding as B
+    L = B.lib()
+    N, H, C = BATCH, 15, 64
+    x = torch.randn(N, H, H, C, device=dev)
+    w = torch.randn(5, 5, C, C, device=dev) * 0.05
+    b = torch.zeros(C, device=dev)
+    y = torch.empty(N, H, H, C, device=dev)
+    fn = lambda s: L.dsspk_conv_fwd(s, x.data_ptr(), w.data_ptr(), b.data_ptr(), y.data_ptr(), N, H, H, C, C, 5, 5, 1, 2, 1, None)
+    flops = 2.0 * N * H * H * C * 25 * C
+    return ("alexnet_conv2_fwd", "conv 5x5 forward + bias + ReLU 64->64 @15x15, batch %d (implicit GEMM)" % N, flops,
+            2 * 4.0 * N * H * H * C, fn, None, ("k_conv.hip", "mma.hpp"), (x, w, b, y))
+
+
 def measure(workload, em):
     """(dominant kernel entry, list of the other entries).  The kernel with the largest share of GPU time in the
     ResNet-110 profile is the fused d-input convolution of the first stage; for the server stress it is the apply kernel."""
@@ -217,7 +233,9 @@ def measure(workload, em):
     if workload == "resnet110":
         top = "conv_dgrad_bn_32x32x16"
     elif workload == "alexnet_ds":
-        top = "conv_fwd_8x8x64"
+        case = _alexnet_conv2_case(em.dev)
+        top = case[0]
+        allm[top] = _entry(case, _time(case[4], em.streams[0]))
     else:
         top = "apply_%d" % em.n
     return allm[top], [v for k, v in allm.items() if k != top]

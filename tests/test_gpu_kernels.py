@@ -58,7 +58,7 @@ def test_fc_forward_backward(oracle_nn, m, n_in, n_out):
     rc(L.dsspk_gemm(s, X.data_ptr(), n_in, 1, W.data_ptr(), n_out, 1, y.data_ptr(), n_out, m, n_out, n_in, Bv.data_ptr(), 0))
     rc(L.dsspk_gemm(s, DY.data_ptr(), n_out, 1, W.data_ptr(), 1, n_out, dx.data_ptr(), n_in, m, n_in, n_out, None, 0))
     rc(L.dsspk_gemm(s, X.data_ptr(), 1, n_in, DY.data_ptr(), n_out, 1, dw.data_ptr(), n_out, n_in, n_out, m, None, 0))
-    rc(L.dsspk_colsum(s, DY.data_ptr(), db.data_ptr(), m, n_out))
+    rc(L.dsspk_colsum(s, DY.data_ptr(), db.data_ptr(), None, m, n_out))
     x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
     yo = oracle_nn.fc_fwd(x64, w64, b.astype(np.float64))
     dxo, dwo, dbo = oracle_nn.fc_bwd(x64, w64, dy64)
@@ -69,6 +69,23 @@ def test_fc_forward_backward(oracle_nn, m, n_in, n_out):
     yr = empty((m, n_out))
     rc(L.dsspk_gemm(s, X.data_ptr(), n_in, 1, W.data_ptr(), n_out, 1, yr.data_ptr(), n_out, m, n_out, n_in, Bv.data_ptr(), 1))
     assert rel_l2(host(yr), np.maximum(yo, 0)) < TOL
+
+
+@pytest.mark.parametrize("M,N", [(1, 1), (1024, 64), (1025, 64), (131072, 64), (28800, 64), (5000, 100)])
+def test_column_sums_of_tall_matrices(M, N):
+    """Bias gradients of the convolutions: one pass for short matrices, row slabs + their sum for tall ones."""
+    g = np.random.default_rng(M + N)
+    x = f32(g, (M, N))
+    L = B.lib()
+    s = stream_ptr()
+    X = dev(x); out = empty(N)
+    need = L.dsspk_colsum_scratch_floats(M, N)
+    assert (need > 0) == (M > 1024)
+    scr = empty(max(1, need))
+    rc(L.dsspk_colsum(s, X.data_ptr(), out.data_ptr(), scr.data_ptr() if need else None, M, N))
+    assert rel_l2(host(out), x.astype(np.float64).sum(0)) < TOL
+    if need:
+        assert L.dsspk_colsum(s, X.data_ptr(), out.data_ptr(), None, M, N) == -1
 
 
 # ------------------------------------------------------------------ convolution
