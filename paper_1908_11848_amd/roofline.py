@@ -16,10 +16,13 @@ F = 2 * N * H * H * C * 9 * C FLOP (one 3x3 convolution):
     conv_fwd       plain forward convolution + statistics records            F,  2 T  (read x, write y)
     conv_fwd_bn    records merge + forward convolution with BN + shortcut    F,  4 T  (read z, shortcut; write a, y)
                    + ReLU folded into its loader (2 kernels)
-    conv_dgrad_bn  d-input convolution with BN backward in its loader,       F,  7 T  (read dz, xc, add, mask source,
-                   shortcut gradient, ReLU mask + sum records in its                  xc of the next BN; write dx, out)
-                   epilogue, carrying a d-filter reduction                       + the reduction's partial sums
-    conv_wgrad     d-filter convolution, stage 1, carrying the BN sums job   F,  2 T + its partial sums
+    conv_bwd_fused d-input AND d-filter convolution of a layer in one kernel 2F, 6 T  (read dz, xc, add, x, xc of the next BN;
+                   (stages 1-2): BN backward in its loader, shortcut                  write out) + its own partial sums and
+                   gradient, ReLU mask + sum records in its epilogue,                 the carried reduction's
+                   carrying the previous layer's d-filter reduction
+    conv_dgrad_bn  the same without the d-filter part (stage 3), dx stored   F,  7 T  + the carried reduction's partial sums
+    conv_wgrad     d-filter convolution, stage 1 (stage 3), carrying the     F,  2 T + its partial sums
+                   BN sums job
     bn_fwd / bn_bwd  stand-alone batch-norm kernels (irregular layers only)      4 T / 7 T
     apply / pull   server update and snapshot copy                               12 / 8 bytes per parameter
 A case is bound by whichever of its two floors is higher: F at 157.3 TFLOP/s (fp32 matrix cores: 256 CUs
@@ -41,7 +44,6 @@ _COUNTERS = os.path.join(os.path.dirname(_HERE), "profiles", "traffic_counters.j
 STAGES = ((32, 16), (16, 32), (8, 64))      # (height = width, channels) of the three ResNet stages
 BATCH = 128
 N_PARAMS = 1_733_812                         # ResNet-110, 10 classes
-CONV_KINDS = ("conv_fwd", "conv_fwd_bn", "conv_dgrad_bn", "conv_wgrad")
 SOURCES = ("k_conv3x3.hip", "k_conv.hip", "k_elem.hip", "k_server.hip", "jobs.hpp", "bn_merge.hpp", "mma.hpp")
 
 
@@ -49,8 +51,11 @@ def case_list(n_params=N_PARAMS):
     """[(key, kernels per launch, kernels launched once beforehand)] in launch order; no GPU needed."""
     out = []
     for H, C in STAGES:
-        out += [("conv_fwd_%dx%dx%d" % (H, H, C), 1, 0), ("conv_fwd_bn_%dx%dx%d" % (H, H, C), 2, 1),
-                ("conv_dgrad_bn_%dx%dx%d" % (H, H, C), 1, 1), ("conv_wgrad_%dx%dx%d" % (H, H, C), 1, 0)]
+        out += [("conv_fwd_%dx%dx%d" % (H, H, C), 1, 0), ("conv_fwd_bn_%dx%dx%d" % (H, H, C), 2, 1)]
+        if C < 64:
+            out += [("conv_bwd_fused_%dx%dx%d" % (H, H, C), 1, 0)]
+        else:
+            out += [("conv_dgrad_bn_%dx%dx%d" % (H, H, C), 1, 1), ("conv_wgrad_%dx%dx%d" % (H, H, C), 1, 0)]
     out += [("bn_fwd_32x32x16", 2, 0), ("bn_bwd_32x32x16", 2, 2)]
     for n in sorted({n_params, 25_000_000}):
         out += [("apply_%d" % n, 1, 0), ("pull_%d" % n, 1, 0)]
@@ -130,13 +135,24 @@ def _conv_cases(H, C, dev):
                                                   dx.data_ptr(), w.data_ptr(), add.data_ptr(), add.data_ptr(), act.data_ptr(),
                                                   xcp.data_ptr(), stats.data_ptr(), rec.data_ptr(), scr.data_ptr(), dw.data_ptr(),
                                                   E, chunks, N, H, C)
-    keep = (x, z, sc, a, y, dz, xc, add, act, xcp, dx, w, gamma, beta, stats, stats_o, tot, dgam, dbet, recA, recB, rec, scr, dw, ch)
+    scr2 = torch.zeros_like(scr)
+    fused = lambda s: L.dsspk_conv_bwd_data_bn_wgrad(s, dz.data_ptr(), xc.data_ptr(), stats.data_ptr(), gamma.data_ptr(), tot.data_ptr(),
+                                                     w.data_ptr(), add.data_ptr(), add.data_ptr(), xcp.data_ptr(), stats.data_ptr(),
+                                                     rec.data_ptr(), act.data_ptr(), scr.data_ptr(), scr2.data_ptr(), dw.data_ptr(),
+                                                     E, chunks, N, H, C)
+    keep = (x, z, sc, a, y, dz, xc, add, act, xcp, dx, w, gamma, beta, stats, stats_o, tot, dgam, dbet, recA, recB, rec, scr, scr2, dw, ch)
     part_bytes = 4.0 * chunks * E
     desc = "%d->%d @%dx%d, batch %d" % (C, C, H, H, N)
-    return [
+    head = [
         ("conv_fwd_%dx%dx%d" % (H, H, C), "conv 3x3 forward + statistics records " + desc, F, 2 * T, fwd, None, keep),
         ("conv_fwd_bn_%dx%dx%d" % (H, H, C), "records merge + conv 3x3 forward with BN, shortcut, ReLU in its loader " + desc,
-         F, 4 * T, fwd_bn, fwd, keep),
+         F, 4 * T, fwd_bn, fwd, keep)]
+    if C < 64:
+        return head + [
+            ("conv_bwd_fused_%dx%dx%d" % (H, H, C), "conv 3x3 d-input + d-filter in one kernel: BN backward in its loader, shortcut "
+             "gradient, ReLU mask + sum records in its epilogue, carrying a d-filter reduction " + desc,
+             2 * F, 6 * T + 2 * part_bytes + 4.0 * E, fused, None, keep)]
+    return head + [
         ("conv_dgrad_bn_%dx%dx%d" % (H, H, C), "conv 3x3 d-input with BN backward in its loader, shortcut gradient, ReLU mask + "
          "sum records in its epilogue, carrying a d-filter reduction " + desc, F, 7 * T + part_bytes + 4.0 * E, dgrad_bn, wgrad, keep),
         ("conv_wgrad_%dx%dx%d" % (H, H, C), "conv 3x3 d-filter stage 1, carrying the BN sums " + desc, F, 2 * T + part_bytes, wgrad, None, keep),
@@ -228,10 +244,10 @@ def _alexnet_conv2_case(dev):
 
 def measure(workload, em):
     """(dominant kernel entry, list of the other entries).  The kernel with the largest share of GPU time in the
-    ResNet-110 profile is the fused d-input convolution of the first stage; for the server stress it is the apply kernel."""
+    ResNet-110 profile is the fused backward convolution kernel of the first stage; for the server stress it is the apply kernel."""
     allm = measure_all(em.dev, em.streams[0], em.n)
     if workload == "resnet110":
-        top = "conv_dgrad_bn_32x32x16"
+        top = "conv_bwd_fused_32x32x16"
     elif workload == "alexnet_ds":
         case = _alexnet_conv2_case(em.dev)
         top = case[0]
