@@ -24,7 +24,7 @@ pytestmark = pytest.mark.gpu
 
 from paper_1908_11848_amd import binding as B, inputs          # noqa: E402
 from paper_1908_11848_amd.emulation import Emulation           # noqa: E402
-from gpu_util import rel_l2                                     # noqa: E402
+from gpu_util import gradient_parity, rel_l2                    # noqa: E402
 from oracle import dssp_rules as R, ps                          # noqa: E402
 
 GRAD_TOL, WEIGHT_TOL = 1e-4, 1e-3
@@ -32,43 +32,6 @@ GRAD_TOL, WEIGHT_TOL = 1e-4, 1e-3
 
 def say(*a):
     print(*a, flush=True)
-
-
-def gradient_parity(net, em, p, w_local, x, y):
-    """Steps (1)-(3) of the module docstring for worker p's last step.  Returns (rel err, #ties)."""
-    loss_o, g_o, trace = net.loss_and_grad(w_local, x, y)
-    g_gpu, loss_gpu = em.worker_grad(p)
-    tie, nflip = {}, 0
-    i = 0
-    while ("relu", i) in trace:
-        z, act = trace[("relu", i)]["z"], trace[("relu", i)]["active"].astype(bool)
-        a_gpu = em.workspace_tensor(p, 0, i).reshape(z.shape)
-        err = np.abs(a_gpu - np.maximum(z, 0))
-        assert err.max() <= 2e-5 * (1 + np.abs(z).max()), ("forward activation", i, err.max())
-        diff = (a_gpu > 0) != act
-        if diff.any():
-            forced = np.full(z.shape, -1, dtype=np.int8)
-            forced[diff] = (a_gpu > 0)[diff]
-            tie[("relu", i)] = forced
-            nflip += int(diff.sum())
-        i += 1
-    i = 0
-    while ("pool", i) in trace:
-        arg = trace[("pool", i)]["arg"]
-        arg_gpu = em.workspace_tensor(p, 1, i).reshape(arg.shape).astype(np.int32)
-        diff = arg_gpu != arg
-        if diff.any():
-            forced = np.full(arg.shape, -1, dtype=np.int32)
-            forced[diff] = arg_gpu[diff]
-            tie[("pool", i)] = forced
-            nflip += int(diff.sum())
-        i += 1
-    logits_gpu = em.workspace_tensor(p, 2, 0).reshape(trace["logits"].shape)
-    assert rel_l2(logits_gpu, trace["logits"]) < 2e-5
-    assert abs(loss_gpu - loss_o) < 2e-5 * max(1.0, abs(loss_o))
-    if tie:
-        _, g_o, _ = net.loss_and_grad(w_local, x, y, tie_break=tie)     # raises unless every forced decision is a near-tie
-    return rel_l2(g_gpu, g_o), nflip
 
 
 def segs_of(model, n_classes):
