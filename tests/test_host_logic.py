@@ -128,3 +128,18 @@ def test_oracle_is_not_imported_by_the_product():
             assert "oracle" not in open(os.path.join(pkg, fn)).read(), fn
     for fn in os.listdir(os.path.join(pkg, "csrc")):
         assert "oracle" not in open(os.path.join(pkg, "csrc", fn)).read(), fn
+
+
+def test_paradigm_sweep_in_virtual_time():
+    """The library's controller alone on the heterogeneous tables: the looser the paradigm, the sooner the server has
+    its pushes (Sec. V-B: ASP fastest, BSP slowest, DSSP between SSP at its two bounds), workers never wait under ASP,
+    and the staleness a worker is allowed to go on with respects each paradigm's bound."""
+    from paper_1908_11848_amd import paradigms
+    for config, K in ((3, 4), (4, 8)):
+        res = dict(paradigms.sweep(config, K, 100 * K))
+        rate = {k: v["pushes_per_unit_time"] for k, v in res.items()}
+        assert rate["ASP"] >= rate["SSP s=15"] >= rate["DSSP (3,12)"] >= rate["SSP s=3"] >= rate["BSP"] > 0
+        assert res["ASP"]["wait_fraction"] == 0 and res["BSP"]["wait_fraction"] > res["DSSP (3,12)"]["wait_fraction"] > 0
+        assert res["BSP"]["staleness_max"] == 0 and res["SSP s=3"]["staleness_max"] <= 3
+        assert res["SSP s=15"]["staleness_max"] <= 15 and res["DSSP (3,12)"]["staleness_max"] <= 15
+        assert all(v["pushes"] == 100 * K for v in res.values())
