@@ -69,7 +69,7 @@ def main():
         em = Emulation(wl["model"], K, wl["s_L"], wl["r_max"], wl["lr"], w0, wl["batch"], wl["n_classes"], xs, ys,
                        worker_streams=a.worker_streams)
         n = int(w0.size)
-    sched = em.schedule(d, log=False)
+    sched = em.schedule(d, log=False, fused_pull=True)       # the pull of a worker granted OK by its own push rides in the apply kernel
     sched.advance(a.warmup)
     em.synchronize()
     torch.cuda.synchronize()

@@ -120,6 +120,18 @@ int dssp_worker_step(dssp_ctx* ctx, int worker, const float* x_dev, const int32_
 int dssp_push(dssp_ctx* ctx, int worker, const float* grad_dev, int64_t t_push_ticks,
               int* ok_out, int* released_out, int* n_released_out, int* rstar_out, int* grant_out);
 
+/* dssp_push whose apply also serves as the pusher's next pull when the pusher is granted OK at once (Alg. 1, server
+ * step 2 and worker steps 2-3 in one pass over the weights: 16 instead of 20 bytes per parameter).  Decisions,
+ * counters and results are those of dssp_push followed by dssp_pull(worker, pull_dst_dev).
+ *   pull_dst_dev     where the pusher's snapshot goes (n_params floats, 16-byte aligned; ignored by a host-only context)
+ *   pulled_out       1 = the snapshot of version *version_out has been enqueued into pull_dst_dev: the worker goes
+ *                    straight to its next dssp_worker_step; 0 = the worker was blocked, only the apply was enqueued,
+ *                    and it pulls with dssp_pull once a later push releases it
+ *   version_out      (may be NULL) number of applies including this one */
+int dssp_push_pull(dssp_ctx* ctx, int worker, const float* grad_dev, int64_t t_push_ticks, float* pull_dst_dev,
+                   int* ok_out, int* released_out, int* n_released_out, int* rstar_out, int* grant_out,
+                   int* pulled_out, uint64_t* version_out);
+
 /* Read-only view of the server's counters (Alg. 1 preamble): t[K] pushes received,
  * r[K] remaining extra-iteration credit, blocked[K] 1 while waiting for OK, version = number
  * of applies.  Any output may be NULL. */

@@ -22,6 +22,10 @@ int dsspk_apply(void* stream, float* w_dev, const float* g_dev, int64_t n, float
 /* Worker steps 2-3: dst[i] = w[i]; *dst_stamp_dev = *stamp_dev. */
 int dsspk_pull(void* stream, float* dst_dev, const float* w_dev, int64_t n,
                uint64_t* dst_stamp_dev, const uint64_t* stamp_dev);
+/* apply and pull in one pass (16 B/param): w -= scale * g, the new w also written to dst_dev, both stamps = version.
+ * Results are bit-identical to dsspk_apply followed by dsspk_pull.  dst_stamp_dev may be NULL. */
+int dsspk_apply_pull(void* stream, float* w_dev, const float* g_dev, float* dst_dev, int64_t n, float scale,
+                     uint64_t* stamp_dev, uint64_t* dst_stamp_dev, uint64_t version);
 
 /* C[M][N] = op(A)[M][K] * op(B)[K][N] (+ bias[N]) (ReLU if relu).  Element (i,k) of op(A) is
  * A[i*a_rs + k*a_cs], element (k,j) of op(B) is B[k*b_rs + j*b_cs]; C is row-major with

@@ -45,6 +45,8 @@ _SIGNATURES = {
     "dssp_pull": (c_int, [c_void_p, c_int, c_void_p, P(ctypes.c_uint64)]),
     "dssp_worker_step": (c_int, [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "dssp_push": (c_int, [c_void_p, c_int, c_void_p, c_int64, P(c_int), P(c_int), P(c_int), P(c_int), P(c_int)]),
+    "dssp_push_pull": (c_int, [c_void_p, c_int, c_void_p, c_int64, c_void_p, P(c_int), P(c_int), P(c_int), P(c_int), P(c_int),
+                               P(c_int), P(ctypes.c_uint64)]),
     "dssp_clock": (c_int, [c_void_p, P(c_int64), P(ctypes.c_int32), P(ctypes.c_uint8), P(ctypes.c_uint64)]),
     "dssp_device_stamps": (c_int, [c_void_p, P(ctypes.c_uint64)]),
     "dssp_synchronize": (c_int, [c_void_p]),
@@ -57,6 +59,7 @@ _SIGNATURES = {
     # include/dssp_kernels.h
     "dsspk_apply": (c_int, [c_void_p, c_void_p, c_void_p, c_int64, c_float, c_void_p, ctypes.c_uint64]),
     "dsspk_pull": (c_int, [c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p]),
+    "dsspk_apply_pull": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, ctypes.c_float, c_void_p, c_void_p, ctypes.c_uint64]),
     "dsspk_gemm": (c_int, [c_void_p, c_void_p, c_long, c_long, c_void_p, c_long, c_long, c_void_p, c_long,
                            c_int, c_int, c_int, c_void_p, c_int]),
     "dsspk_colsum": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_long, c_int]),
@@ -159,6 +162,18 @@ def dssp_push(ctx, worker, grad_dev, t_push_ticks, K):
     _check(ctx, lib().dssp_push(ctx, worker, ptr(grad_dev), int(t_push_ticks), ctypes.byref(ok), rel,
                                 ctypes.byref(n_rel), ctypes.byref(rstar), ctypes.byref(grant)))
     return bool(ok.value), list(rel[:n_rel.value]), rstar.value, grant.value
+
+
+def dssp_push_pull(ctx, worker, grad_dev, t_push_ticks, K, pull_dst_dev):
+    """-> (ok, released list, r*, grant, pulled, version): as dssp_push; pulled = the pusher's snapshot of the new
+    weights was written to pull_dst_dev by the same kernel (it was granted OK), so it must not call dssp_pull."""
+    ok, n_rel, rstar, grant, pulled = c_int(), c_int(), c_int(), c_int(), c_int()
+    v = ctypes.c_uint64()
+    rel = (c_int * K)()
+    _check(ctx, lib().dssp_push_pull(ctx, worker, ptr(grad_dev), int(t_push_ticks), ptr(pull_dst_dev), ctypes.byref(ok), rel,
+                                     ctypes.byref(n_rel), ctypes.byref(rstar), ctypes.byref(grant), ctypes.byref(pulled),
+                                     ctypes.byref(v)))
+    return bool(ok.value), list(rel[:n_rel.value]), rstar.value, grant.value, bool(pulled.value), v.value
 
 
 def dssp_clock(ctx, K):

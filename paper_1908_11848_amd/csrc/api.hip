@@ -251,8 +251,12 @@ extern "C" int dssp_worker_step(dssp_ctx* c, int worker, const float* x_dev, con
     return DSSP_OK;
 }
 
-extern "C" int dssp_push(dssp_ctx* c, int worker, const float* grad_dev, int64_t t_push, int* ok_out,
-                         int* released_out, int* n_released_out, int* rstar_out, int* grant_out) {
+// Alg. 1 server part for one push.  The decision (steps 3-16 and Alg. 2) is integer work on the host and does not
+// depend on the apply, so it is taken first; the device work enqueued afterwards is the apply alone, or - if the
+// pusher may go on at once and handed over where its next snapshot goes - apply and pull in one kernel.
+static int push_impl(dssp_ctx* c, int worker, const float* grad_dev, int64_t t_push, float* pull_dst_dev, int* ok_out,
+                     int* released_out, int* n_released_out, int* rstar_out, int* grant_out, int* pulled_out,
+                     uint64_t* version_out) {
     if (int rc = check_worker(c, worker)) return rc;
     if (!ok_out || !released_out || !n_released_out) return fail(c, DSSP_EINVAL, "null output pointer");
     if (c->blocked[worker] || !c->has_ok[worker])
@@ -262,23 +266,12 @@ extern "C" int dssp_push(dssp_ctx* c, int worker, const float* grad_dev, int64_t
         if (!grad_dev) return fail(c, DSSP_EINVAL, "grad_dev is null");
         if (int rc = ensure_stream(c, p)) return rc;
         if (int rc = ensure_stream(c, -1)) return rc;
-        // the apply runs behind the worker's gradient and behind every snapshot still reading w
-        HIP_TRY(c, hipEventRecord(c->ev_grad[p], c->wstream[p]));
-        HIP_TRY(c, hipStreamWaitEvent(c->server_stream, c->ev_grad[p], 0));
-        for (int q = 0; q < c->K; ++q)
-            if (c->pull_pending[q]) {
-                HIP_TRY(c, hipStreamWaitEvent(c->server_stream, c->ev_pull[q], 0));
-                c->pull_pending[q] = 0;
-            }
-        if (int rc = dsspk_apply(c->server_stream, c->params, grad_dev, c->n_params, c->scale, c->stamps_dev, c->version + 1))
-            return fail(c, DSSP_EHIP, "apply kernel launch failed (rc " + std::to_string(rc) + ")");
-        HIP_TRY(c, hipEventRecord(c->ev_apply, c->server_stream));
     }
     // Alg. 2 steps 1-2, done for every push so that A really holds the two latest pushes of all workers
     c->A[p][1] = c->A[p][0];
     c->A[p][0] = t_push;
     c->t[p] += 1;            // Alg. 1 server step 1
-    c->version += 1;         // Alg. 1 server step 2 (the apply enqueued above)
+    c->version += 1;         // Alg. 1 server step 2 (the apply enqueued below)
     int r_star = -1, grant = -1;
     bool ok;
     if (c->r[p] > 0) {       // steps 3-5: spend one unit of credit
@@ -310,11 +303,49 @@ extern "C" int dssp_push(dssp_ctx* c, int worker, const float* grad_dev, int64_t
             c->has_ok[q] = 1;
             released_out[n_rel++] = q;
         }
+    const bool fused = ok && pull_dst_dev != nullptr;
+    if (!c->host_only) {
+        // the apply runs behind the worker's gradient and behind every snapshot still reading w
+        HIP_TRY(c, hipEventRecord(c->ev_grad[p], c->wstream[p]));
+        HIP_TRY(c, hipStreamWaitEvent(c->server_stream, c->ev_grad[p], 0));
+        for (int q = 0; q < c->K; ++q)
+            if (c->pull_pending[q]) {
+                HIP_TRY(c, hipStreamWaitEvent(c->server_stream, c->ev_pull[q], 0));
+                c->pull_pending[q] = 0;
+            }
+        int rc;
+        if (fused)      // the worker's stream gets at the snapshot through ev_apply, like at any other pull
+            rc = dsspk_apply_pull(c->server_stream, c->params, grad_dev, pull_dst_dev, c->n_params, c->scale, c->stamps_dev,
+                                  c->stamps_dev + 1 + p, c->version);
+        else
+            rc = dsspk_apply(c->server_stream, c->params, grad_dev, c->n_params, c->scale, c->stamps_dev, c->version);
+        if (rc) return fail(c, DSSP_EHIP, "apply kernel launch failed (rc " + std::to_string(rc) + ")");
+        HIP_TRY(c, hipEventRecord(c->ev_apply, c->server_stream));
+        if (fused) HIP_TRY(c, hipStreamWaitEvent(c->wstream[p], c->ev_apply, 0));
+    }
     *ok_out = ok ? 1 : 0;
     *n_released_out = n_rel;
     if (rstar_out) *rstar_out = r_star;
     if (grant_out) *grant_out = grant;
+    if (pulled_out) *pulled_out = fused ? 1 : 0;
+    if (version_out) *version_out = c->version;
     return DSSP_OK;
+}
+
+extern "C" int dssp_push(dssp_ctx* c, int worker, const float* grad_dev, int64_t t_push, int* ok_out,
+                         int* released_out, int* n_released_out, int* rstar_out, int* grant_out) {
+    return push_impl(c, worker, grad_dev, t_push, nullptr, ok_out, released_out, n_released_out, rstar_out, grant_out, nullptr,
+                     nullptr);
+}
+
+extern "C" int dssp_push_pull(dssp_ctx* c, int worker, const float* grad_dev, int64_t t_push, float* pull_dst_dev, int* ok_out,
+                              int* released_out, int* n_released_out, int* rstar_out, int* grant_out, int* pulled_out,
+                              uint64_t* version_out) {
+    if (c && !c->host_only && !pull_dst_dev) return fail(c, DSSP_EINVAL, "pull_dst_dev is null");
+    if (!pulled_out) return c ? fail(c, DSSP_EINVAL, "null output pointer") : DSSP_EINVAL;
+    static float host_only_dst;           // a host-only context takes the same decisions; the pointer is never used
+    return push_impl(c, worker, grad_dev, t_push, (c && c->host_only) ? &host_only_dst : pull_dst_dev, ok_out, released_out,
+                     n_released_out, rstar_out, grant_out, pulled_out, version_out);
 }
 
 extern "C" int dssp_clock(dssp_ctx* c, int64_t* t_out, int32_t* r_out, uint8_t* blocked_out, uint64_t* version_out) {

@@ -20,11 +20,13 @@ PUSH, CTRL, OK, BLOCK, RELEASE, PULL = 0, 1, 2, 3, 4, 5
 class Schedule:
     """Resumable schedule: advance(n) processes the next n pushes."""
 
-    def __init__(self, ctx, K, durations, quota=None, grad_ptr=None, pull_dst=None, step=None, log=True):
+    def __init__(self, ctx, K, durations, quota=None, grad_ptr=None, pull_dst=None, step=None, log=True, fused_pull=False):
         """grad_ptr(p) -> device pointer of worker p's gradient (None for a host-only context);
         pull_dst(p) -> device pointer of its local weights; step(p, n) enqueues worker p's n-th
-        iteration (dssp_worker_step) or is None."""
+        iteration (dssp_worker_step) or is None.  fused_pull: pushes go through dssp_push_pull, i.e. a worker
+        that is granted OK by its own push gets its snapshot from the apply kernel (same log, same results)."""
         self.ctx, self.K, self.d, self.quota = ctx, K, durations, quota
+        self.fused_pull = fused_pull
         self.gp = grad_ptr or (lambda p: None)
         self.pd = pull_dst or (lambda p: None)
         self.step = step
@@ -42,10 +44,10 @@ class Schedule:
                 step(p, 0)
             heapq.heappush(self.heap, (int(durations[p][0]), p))
 
-    def _start_next(self, q, T, tq, rq):
+    def _start_next(self, q, T, tq, rq, pulled_version=None):
         if self.quota is not None and tq >= self.quota:
             return
-        v = B.dssp_pull(self.ctx, q, self.pd(q))
+        v = pulled_version if pulled_version is not None else B.dssp_pull(self.ctx, q, self.pd(q))
         self.pulled[q] = v
         if self.log is not None:
             self.log.append((PULL, q, T, tq, rq, v, v, 0))
@@ -61,7 +63,13 @@ class Schedule:
         while self.heap and done < n_pushes:
             T, p = heapq.heappop(self.heap)
             self.T_end = T
-            ok, released, rstar, grant = B.dssp_push(self.ctx, p, self.gp(p), T, K)
+            pulled_version = None
+            if self.fused_pull and not (self.quota is not None and self.count[p] + 1 >= self.quota):
+                ok, released, rstar, grant, pulled, v_now = B.dssp_push_pull(self.ctx, p, self.gp(p), T, K, self.pd(p))
+                if pulled:
+                    pulled_version = v_now
+            else:
+                ok, released, rstar, grant = B.dssp_push(self.ctx, p, self.gp(p), T, K)
             self.version += 1
             self.count[p] += 1
             done += 1
@@ -74,7 +82,7 @@ class Schedule:
             else:
                 t, r = self.count, [0] * K
             if ok:
-                self._start_next(p, T, t[p], r[p])
+                self._start_next(p, T, t[p], r[p], pulled_version)
             for q in released:
                 if log is not None:
                     log.append((RELEASE, q, T, t[q], r[q], self.version, 0, 0))
@@ -82,11 +90,11 @@ class Schedule:
         return done
 
 
-def run_schedule(ctx, K, durations, quota=None, total=None, grad_ptr=None, pull_dst=None, step=None, log=True):
+def run_schedule(ctx, K, durations, quota=None, total=None, grad_ptr=None, pull_dst=None, step=None, log=True, fused_pull=False):
     """Runs a whole schedule: until `total` pushes were applied and / or every worker made
     `quota` pushes.  Returns (log, stats)."""
     if quota is None and total is None:
         raise ValueError("need quota or total")
-    s = Schedule(ctx, K, durations, quota=quota, grad_ptr=grad_ptr, pull_dst=pull_dst, step=step, log=log)
+    s = Schedule(ctx, K, durations, quota=quota, grad_ptr=grad_ptr, pull_dst=pull_dst, step=step, log=log, fused_pull=fused_pull)
     s.advance(total if total is not None else K * quota)
     return s.log, dict(T_end=s.T_end, pushes=s.version)

@@ -69,16 +69,17 @@ class Emulation:
         if self.on_step:
             self.on_step(p, n)
 
-    def run(self, durations, quota=None, total=None, log=True):
+    def run(self, durations, quota=None, total=None, log=True, fused_pull=False):
+        """fused_pull: a worker granted OK by its own push takes its snapshot from the apply kernel (dssp_push_pull)."""
         out = driver.run_schedule(self.ctx, self.K, durations, quota=quota, total=total,
                                   grad_ptr=lambda p: self.grad[p], pull_dst=lambda p: self.w_local[p],
-                                  step=self.step, log=log)
+                                  step=self.step, log=log, fused_pull=fused_pull)
         return out
 
-    def schedule(self, durations, quota=None, log=True):
+    def schedule(self, durations, quota=None, log=True, fused_pull=False):
         """Resumable form of run(): returns a driver.Schedule (all workers pulled and started)."""
         return driver.Schedule(self.ctx, self.K, durations, quota=quota, grad_ptr=lambda p: self.grad[p],
-                               pull_dst=lambda p: self.w_local[p], step=self.step, log=log)
+                               pull_dst=lambda p: self.w_local[p], step=self.step, log=log, fused_pull=fused_pull)
 
     def synchronize(self):
         B.dssp_synchronize(self.ctx)

@@ -45,6 +45,24 @@ def test_apply_and_pull(n):
     assert host(stamps).tolist() == [7, 7]
 
 
+@pytest.mark.parametrize("n", [3, 1024, 100003])
+def test_apply_and_pull_in_one_pass(n):
+    """w -= scale * g with the new weights also written to a snapshot: the same bits as apply followed by pull."""
+    g = np.random.default_rng(n)
+    w0, gr = f32(g, n), f32(g, n, 1e-2)
+    L = B.lib()
+    s = stream_ptr()
+    W1, W2, G = dev(w0), dev(w0), dev(gr)
+    d1, d2 = empty(n), empty(n)
+    st1 = torch.zeros(2, dtype=torch.int64, device="cuda"); st2 = torch.zeros(2, dtype=torch.int64, device="cuda")
+    rc(L.dsspk_apply(s, W1.data_ptr(), G.data_ptr(), n, 0.37, st1.data_ptr(), 5))
+    rc(L.dsspk_pull(s, d1.data_ptr(), W1.data_ptr(), n, st1[1:].data_ptr(), st1.data_ptr()))
+    rc(L.dsspk_apply_pull(s, W2.data_ptr(), G.data_ptr(), d2.data_ptr(), n, 0.37, st2.data_ptr(), st2[1:].data_ptr(), 5))
+    assert np.array_equal(host(W1), host(W2)) and np.array_equal(host(d1), host(d2)) and np.array_equal(host(d2), host(W2))
+    assert host(st1).tolist() == host(st2).tolist() == [5, 5]
+    assert rel_l2(host(W2), w0.astype(np.float64) - np.float32(0.37).astype(np.float64) * gr.astype(np.float64)) < 1e-6
+
+
 # ------------------------------------------------------------------ GEMM (fully connected layers)
 @pytest.mark.parametrize("m,n_in,n_out", [(32, 3072, 256), (32, 256, 10), (128, 3136, 384), (128, 192, 10),
                                           (128, 64, 100), (37, 100, 75), (1, 16, 1)])

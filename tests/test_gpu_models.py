@@ -176,7 +176,12 @@ def test_resnet8_step_and_50_updates(oracle_nn):
     say("%s: weights after 50 updates %.2e, displacement %.2e" % (model, e, ed))
     assert e < WEIGHT_TOL
     em.close()
-    # several virtual workers per HIP stream (what the benchmark does with 8 workers): same schedule, same bits
+    # the pusher's pull folded into the apply kernel: same schedule, same bits
+    em = Emulation(model, K, 3, 12, 0.05, w0, batch, 100, xs, ys)
+    log, _ = em.run(d, total=50, fused_pull=True)
+    assert log == out["log"] and np.array_equal(em.weights(), w_gpu)
+    em.close()
+    # several virtual workers per HIP stream: same schedule, same bits
     em = Emulation(model, K, 3, 12, 0.05, w0, batch, 100, xs, ys, worker_streams=2)
     log, _ = em.run(d, total=50)
     assert log == out["log"] and np.array_equal(em.weights(), w_gpu)
@@ -263,6 +268,14 @@ def test_server_stress_config5(oracle_nn):
     for p in range(K):
         if stamps[1 + p] == 50:
             assert np.array_equal(em.w_local[p].cpu().numpy(), w_gpu)
+    # (a') the same 50 pushes with the pusher's pull folded into the apply kernel: same log, same bits, same stamps
+    em2 = Emulation("none", K, 3, 15, lr, w0, grads=g)
+    log2, _ = em2.run(d, total=50, fused_pull=True)
+    assert log2 == log and np.array_equal(em2.weights(), w_gpu)
+    assert B.dssp_device_stamps(em2.ctx, K) == stamps
+    for p in range(K):
+        assert np.array_equal(em2.w_local[p].cpu().numpy(), em.w_local[p].cpu().numpy())
+    em2.close()
     em.close()
     # (b) all 10k pushes: schedule bit-exact, weights against the closed form w0 - scale * sum_p count_p g_p
     em = Emulation("none", K, 3, 15, lr, w0, grads=g)

@@ -34,10 +34,10 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert names == set(B._SIGNATURES), names ^ set(B._SIGNATURES)      # binding and headers list the same calls
 
 
-def host_log(K, s_L, r_max, d, quota=None, total=None):
+def host_log(K, s_L, r_max, d, quota=None, total=None, fused_pull=False):
     ctx = B.dssp_create(None, 0, K, s_L, r_max, 0.1)
     try:
-        return driver.run_schedule(ctx, K, d, quota=quota, total=total)[0]
+        return driver.run_schedule(ctx, K, d, quota=quota, total=total, fused_pull=fused_pull)[0]
     finally:
         B.dssp_destroy(ctx)
 
@@ -57,6 +57,8 @@ def test_host_controller_matches_oracle_random(seed):
     quota = 120
     olog, st, _ = R.simulate(K, s_L, r_max, d, quota=quota)
     assert host_log(K, s_L, r_max, d, quota=quota) == olog
+    # pushes through dssp_push_pull (the pusher's pull folded into the apply when it is granted OK): same schedule
+    assert host_log(K, s_L, r_max, d, quota=quota, fused_pull=True) == olog
 
 
 @pytest.mark.parametrize("cfg,K,s_L,r_max,total", [(1, 4, 3, 4, 200), (2, 4, 3, 12, 400), (3, 4, 3, 12, 400),
@@ -66,6 +68,7 @@ def test_host_controller_matches_oracle_on_workload_schedules(cfg, K, s_L, r_max
     d = inputs.durations(cfg, K, total)
     olog, _, _ = R.simulate(K, s_L, r_max, d, total=total)
     assert host_log(K, s_L, r_max, d, total=total) == olog
+    assert host_log(K, s_L, r_max, d, total=total, fused_pull=True) == olog
 
 
 def test_clock_and_state_errors_host_only():
