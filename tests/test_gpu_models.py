@@ -295,6 +295,24 @@ def test_server_stress_config5(oracle_nn):
     em.close()
 
 
+# ------------------------------------------------------------------ ragged shapes
+@pytest.mark.parametrize("model,batch,ncls", [("resnet8", 3, 7), ("resnet14", 1, 3), ("resnet20", 2, 100), ("alexnet_ds", 5, 10),
+                                              ("alexnet_ds", 1, 4), ("mlp", 1, 10), ("mlp", 7, 3)])
+def test_odd_batch_sizes_and_class_counts(oracle_nn, model, batch, ncls):
+    """One step per worker at batch sizes and class counts that fill no tile: gradient parity with the oracle."""
+    K = 2
+    net = oracle_nn.make_net(model, ncls)
+    w0 = inputs.init_weights(segs_of(model, ncls), 4, jitter=0.1)
+    xs, ys = inputs.batches(4, K, 1, batch, ncls, flat=(model == "mlp"))
+    em = Emulation(model, K, 1, 2, 0.01, w0, batch, ncls, xs, ys)
+    for p in range(K):
+        B.dssp_pull(em.ctx, p, em.w_local[p])
+        em.step(p, 0)
+        err, nflip = gradient_parity(net, em, p, w0, xs[p][0], ys[p][0])
+        assert err < GRAD_TOL, (model, batch, ncls, err)
+    em.close()
+
+
 # ------------------------------------------------------------------ graph replay
 def test_graph_replay_is_bit_identical_to_eager(oracle_nn):
     """A worker step runs eagerly the first time it sees a set of buffers, is captured into a HIP graph
