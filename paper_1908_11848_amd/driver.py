@@ -98,3 +98,60 @@ def run_schedule(ctx, K, durations, quota=None, total=None, grad_ptr=None, pull_
     s = Schedule(ctx, K, durations, quota=quota, grad_ptr=grad_ptr, pull_dst=pull_dst, step=step, log=log, fused_pull=fused_pull)
     s.advance(total if total is not None else K * quota)
     return s.log, dict(T_end=s.T_end, pushes=s.version)
+
+
+def run_wallclock(ctx, K, total, grad_ptr, pull_dst, step, done, clock_ns, poll_sleep=None):
+    """The controller fed with REAL push times instead of a table (how the paper's server runs): a worker's push
+    reaches the server when its gradient is actually finished on the device.
+
+    step(p, n) enqueues worker p's n-th iteration and arranges for done(p) to turn true once the device has
+    finished it; clock_ns() is a monotonic clock.  The loop polls the running workers in index order; the first one
+    found finished pushes with T = elapsed microseconds (integer ticks, strictly increasing so that two pushes never
+    share a timestamp), and every worker that thereby holds an OK pulls and starts its next iteration.  Runs until
+    `total` pushes.  Returns the same integer log as Schedule (PUSH / CTRL / OK / BLOCK / RELEASE / PULL records);
+    replaying its (T, worker) sequence through any implementation of the rules must give the same decisions.
+    """
+    log = []
+    running = [False] * K
+    count = [0] * K
+    pulled = [0] * K
+    t0 = clock_ns()
+    last_T = 0
+
+    def start(q, T, tq, rq):
+        v = B.dssp_pull(ctx, q, pull_dst(q))
+        pulled[q] = v
+        log.append((PULL, q, T, tq, rq, v, v, 0))
+        step(q, tq)
+        running[q] = True
+
+    for p in range(K):
+        start(p, 0, 0, 0)
+    pushes = 0
+    while pushes < total:
+        if not any(running):
+            raise RuntimeError("no worker is running: the schedule is stuck")
+        progressed = False
+        for p in range(K):
+            if pushes >= total or not running[p] or not done(p):
+                continue
+            progressed = True
+            running[p] = False
+            T = max(last_T + 1, (clock_ns() - t0) // 1000)
+            last_T = T
+            ok, released, rstar, grant = B.dssp_push(ctx, p, grad_ptr(p), T, K)
+            pushes += 1
+            count[p] += 1
+            t, r, _, v = B.dssp_clock(ctx, K)
+            log.append((PUSH, p, T, t[p], r[p], v, pulled[p], 0))
+            if rstar >= 0:
+                log.append((CTRL, p, T, t[p], r[p], v, rstar, grant))
+            log.append((OK if ok else BLOCK, p, T, t[p], r[p], v, 0, 0))
+            if ok:
+                start(p, T, t[p], r[p])
+            for q in released:
+                log.append((RELEASE, q, T, t[q], r[q], v, 0, 0))
+                start(q, T, t[q], r[q])
+        if not progressed and poll_sleep:
+            poll_sleep()
+    return log, dict(T_end=last_T, pushes=pushes)

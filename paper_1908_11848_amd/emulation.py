@@ -81,6 +81,27 @@ class Emulation:
         return driver.Schedule(self.ctx, self.K, durations, quota=quota, grad_ptr=lambda p: self.grad[p],
                                pull_dst=lambda p: self.w_local[p], step=self.step, log=log, fused_pull=fused_pull)
 
+    def run_wallclock(self, total, min_iteration_us=None):
+        """Runs `total` pushes with the controller fed by real completion times (driver.run_wallclock).
+        min_iteration_us[p]: an iteration of worker p counts as finished only once the device is done with it AND
+        that many microseconds have passed since it started, which makes the emulated cluster heterogeneous without
+        occupying a hardware queue (streams that share one would slow each other down).  Returns (log, stats)."""
+        import time
+        evs = [torch.cuda.Event() for _ in range(self.K)]
+        t_start = [0] * self.K
+        floor_ns = [int(1000 * u) for u in (min_iteration_us or [0] * self.K)]
+
+        def step(p, n):
+            t_start[p] = time.perf_counter_ns()
+            self.step(p, n)
+            evs[p].record(self.streams[p])
+
+        def done(p):
+            return time.perf_counter_ns() - t_start[p] >= floor_ns[p] and evs[p].query()
+
+        return driver.run_wallclock(self.ctx, self.K, total, grad_ptr=lambda p: self.grad[p], pull_dst=lambda p: self.w_local[p],
+                                    step=step, done=done, clock_ns=time.perf_counter_ns)
+
     def synchronize(self):
         B.dssp_synchronize(self.ctx)
 

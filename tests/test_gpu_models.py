@@ -295,6 +295,46 @@ def test_server_stress_config5(oracle_nn):
     em.close()
 
 
+# ------------------------------------------------------------------ controller fed by real push times
+def test_wallclock_driven_schedule_replays_through_the_oracle(oracle_nn):
+    """Pushes happen when the device has really finished a gradient (heterogeneous workers: a floor on the duration of
+    their iterations), so the schedule differs from run to run.  Whatever it was, the oracle fed with the iteration times
+    read back from the log must take the same decisions (bit-exact log) and arrive at the same weights."""
+    K, s_L, r_max, lr, batch, total = 4, 1, 3, 0.01, 32, 80
+    net = oracle_nn.make_net("mlp", 10)
+    w0 = inputs.init_weights(segs_of("mlp", 10), 1, jitter=0.1)
+    xs, ys = inputs.batches(1, K, 6, batch, 10, flat=True)
+    em = Emulation("mlp", K, s_L, r_max, lr, w0, batch, 10, xs, ys)
+    log, st = em.run_wallclock(total, min_iteration_us=[0, 300, 1000, 3000])
+    w_gpu = em.weights()
+    stamps = B.dssp_device_stamps(em.ctx, K)
+    em.close()
+    assert st["pushes"] == total
+    # iteration times as they happened: push time minus the time of the pull that started the iteration
+    d = np.full((K, total + 2), 10**12, dtype=np.int64)
+    started, n_it = {}, [0] * K
+    kinds = {R.PUSH: 0, R.BLOCK: 0}
+    for kind, p, T, tp, rp, v, a0, a1 in log:
+        if kind == R.PULL:
+            started[p] = T
+        elif kind == R.PUSH:
+            d[p][n_it[p]] = T - started[p]
+            assert d[p][n_it[p]] >= 1
+            n_it[p] += 1
+        if kind in kinds:
+            kinds[kind] += 1
+    say("wall-clock schedule: pushes per worker %s, %d blocks, last push at %d us" % (n_it, kinds[R.BLOCK], st["T_end"]))
+    assert n_it[0] >= n_it[3] and kinds[R.BLOCK] > 0                     # the fast worker never falls behind the slow one, and had to wait
+    out = ps.run(K, s_L, r_max, lr, w0, d, ps.model_grad_fn(net, xs, ys), total=total)
+    assert log == out["log"]
+    assert rel_l2(w_gpu, out["w"]) < WEIGHT_TOL
+    pulls = {}
+    for kind, p, T, tp, rp, v, a0, a1 in log:
+        if kind == R.PULL:
+            pulls[p] = a0
+    assert stamps[0] == total and stamps[1:] == [pulls[p] for p in range(K)]
+
+
 # ------------------------------------------------------------------ ragged shapes
 @pytest.mark.parametrize("model,batch,ncls", [("resnet8", 3, 7), ("resnet14", 1, 3), ("resnet20", 2, 100), ("alexnet_ds", 5, 10),
                                               ("alexnet_ds", 1, 4), ("mlp", 1, 10), ("mlp", 7, 3)])
