@@ -19,8 +19,9 @@ sys.path.insert(0, ROOT)
 
 import numpy as np  # noqa: E402
 
-WORKER_STREAMS = 0      # HIP streams the virtual workers are dealt onto; 0: one per worker (measured best: 279 vs
-                        # 249 pushes/s with 8 workers on 4 streams)
+WORKER_STREAMS = 0      # HIP streams the virtual workers are dealt onto; 0: one per hardware queue, each on a queue
+                        # of its own (measured: 327 pushes/s, as with two streams per queue; 291 with eight
+                        # streams as the runtime happens to deal them, 1, 2, 2 and 3 to a queue)
 
 
 def workload(name):
@@ -91,7 +92,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s, batch %d, %d virtual workers, DSSP s_L=%d r_max=%d, %d params"
                                % (wl["model"], wl["batch"], K, wl["s_L"], wl["r_max"], n),
-                   "worker_streams": min(K, a.worker_streams) if a.worker_streams else K},
+                   "worker_streams": len(set(em.streams[:K])), "hardware_queues": em.hardware_queues},
         "weights_finite": finite,
     }
     if not a.no_roofline:

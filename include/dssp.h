@@ -74,10 +74,28 @@ enum {
 int dssp_create(dssp_ctx** out, float* params_dev, int64_t n_params,
                 int K, int s_L, int r_max, float lr);
 
-/* Streams: worker in [0, K) or -1 for the server's apply stream.  hip_stream is a
+/* Streams: worker in [0, K), or -1 for a stream of the server's own.  hip_stream is a
  * hipStream_t created by the caller (default priority); it must outlive the context.
- * Without this call a context creates and owns its streams. */
+ * Worker streams the caller did not set are created and owned by the context.  The server
+ * has no stream unless one is set: each apply then runs on the pusher's stream, right behind
+ * the gradient it consumes, and the context's events keep applies in push order and behind
+ * every snapshot still being read.  With a server stream (nullptr takes it away again) the
+ * applies run there instead, behind the same events; results are identical, but a stream
+ * that shares a hardware queue with a worker's stream makes the small apply wait for that
+ * worker's whole iteration. */
 int dssp_set_stream(dssp_ctx* ctx, int worker, void* hip_stream);
+
+/* Which of n idle streams share a hardware queue (no passage of the paper: a property of the
+ * device runtime that decides how K workers on one GPU should be dealt onto streams).  A process
+ * has few hardware queues and the runtime spreads streams over them unevenly; work on streams of
+ * one queue runs one after the other, so workers should sit on streams of different queues, the
+ * same number on each.  queue_out[i] receives the queue number of hip_streams[i], numbered from 0
+ * in order of first appearance; n_queues_out (may be NULL) the number of queues seen.  Measured,
+ * not looked up: for each pair tested a kernel spins for 2 ms on one stream while a kernel on the
+ * other reads the device clock, so the call takes up to about n * queues * 4 ms and synchronises the given
+ * streams.  n in [1, 64]; the current device is used; needs no context.  Returns DSSP_EINVAL or
+ * DSSP_EHIP on failure. */
+int dssp_stream_queues(void* const* hip_streams, int n, int* queue_out, int* n_queues_out);
 
 /* Selects the network of dssp_worker_step and hands over scratch memory.
  *   workspace_dev    at least dssp_workspace_bytes(...) bytes, 256-byte aligned, caller-owned,

@@ -50,6 +50,7 @@ _SIGNATURES = {
     "dssp_clock": (c_int, [c_void_p, P(c_int64), P(ctypes.c_int32), P(ctypes.c_uint8), P(ctypes.c_uint64)]),
     "dssp_device_stamps": (c_int, [c_void_p, P(ctypes.c_uint64)]),
     "dssp_synchronize": (c_int, [c_void_p]),
+    "dssp_stream_queues": (c_int, [P(c_void_p), c_int, P(c_int), P(c_int)]),
     "dssp_last_error": (ctypes.c_char_p, [c_void_p]),
     "dssp_destroy": (c_int, [c_void_p]),
     "dssp_model_param_count": (c_int64, [c_int, c_int]),
@@ -194,6 +195,18 @@ def dssp_device_stamps(ctx, K):
 
 def dssp_synchronize(ctx):
     _check(ctx, lib().dssp_synchronize(ctx))
+
+
+def dssp_stream_queues(streams):
+    """-> (queue number of each stream, number of hardware queues seen)"""
+    n = len(streams)
+    h = (c_void_p * n)(*[stream_handle(s) for s in streams])
+    q = (c_int * n)()
+    nq = c_int()
+    rc = lib().dssp_stream_queues(h, n, q, ctypes.byref(nq))
+    if rc < 0:
+        raise DsspError(rc, "dssp_stream_queues")
+    return list(q), nq.value
 
 
 def dssp_destroy(ctx):

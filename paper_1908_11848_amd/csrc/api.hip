@@ -32,7 +32,6 @@ struct dssp_ctx {
 
     // device side
     hipStream_t server_stream = nullptr;
-    bool own_server_stream = false;
     std::vector<hipStream_t> wstream;
     std::vector<uint8_t> own_wstream;
     hipEvent_t ev_apply = nullptr;                // last apply finished
@@ -153,13 +152,13 @@ extern "C" int dssp_create(dssp_ctx** out, float* params_dev, int64_t n_params, 
 }
 
 namespace {
-// Streams the caller did not set are created on first use.
+// Worker streams the caller did not set are created on first use.
 int ensure_stream(dssp_ctx* c, int worker) {
     if (c->host_only) return DSSP_OK;
-    hipStream_t& s = worker < 0 ? c->server_stream : c->wstream[worker];
+    hipStream_t& s = c->wstream[worker];
     if (s) return DSSP_OK;
     HIP_TRY(c, hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
-    if (worker < 0) c->own_server_stream = true; else c->own_wstream[worker] = 1;
+    c->own_wstream[worker] = 1;
     return DSSP_OK;
 }
 }  // namespace
@@ -168,11 +167,11 @@ extern "C" int dssp_set_stream(dssp_ctx* c, int worker, void* hip_stream) {
     if (!c) return DSSP_EINVAL;
     if (worker < -1 || worker >= c->K) return fail(c, DSSP_EINVAL, "worker index out of range");
     if (c->host_only) return DSSP_OK;
-    hipStream_t& s = worker < 0 ? c->server_stream : c->wstream[worker];
-    const bool owned = worker < 0 ? c->own_server_stream : (bool)c->own_wstream[worker];
-    if (owned && s) { HIP_TRY(c, hipStreamSynchronize(s)); HIP_TRY(c, hipStreamDestroy(s)); }
+    if (worker < 0) { c->server_stream = (hipStream_t)hip_stream; return DSSP_OK; }
+    hipStream_t& s = c->wstream[worker];
+    if (c->own_wstream[worker] && s) { HIP_TRY(c, hipStreamSynchronize(s)); HIP_TRY(c, hipStreamDestroy(s)); }
     s = (hipStream_t)hip_stream;
-    if (worker < 0) c->own_server_stream = false; else c->own_wstream[worker] = 0;
+    c->own_wstream[worker] = 0;
     return DSSP_OK;
 }
 
@@ -265,7 +264,6 @@ static int push_impl(dssp_ctx* c, int worker, const float* grad_dev, int64_t t_p
     if (!c->host_only) {
         if (!grad_dev) return fail(c, DSSP_EINVAL, "grad_dev is null");
         if (int rc = ensure_stream(c, p)) return rc;
-        if (int rc = ensure_stream(c, -1)) return rc;
     }
     // Alg. 2 steps 1-2, done for every push so that A really holds the two latest pushes of all workers
     c->A[p][1] = c->A[p][0];
@@ -305,23 +303,31 @@ static int push_impl(dssp_ctx* c, int worker, const float* grad_dev, int64_t t_p
         }
     const bool fused = ok && pull_dst_dev != nullptr;
     if (!c->host_only) {
-        // the apply runs behind the worker's gradient and behind every snapshot still reading w
-        HIP_TRY(c, hipEventRecord(c->ev_grad[p], c->wstream[p]));
-        HIP_TRY(c, hipStreamWaitEvent(c->server_stream, c->ev_grad[p], 0));
+        // The apply runs behind the worker's gradient, behind the apply before it and behind every snapshot still
+        // reading w.  Without a server stream it goes onto the pusher's own stream, right behind the gradient: a
+        // separate stream shares a hardware queue with some worker's stream, and the small apply then waits for
+        // that worker's whole iteration.
+        const bool own = c->server_stream == nullptr;
+        hipStream_t as = own ? c->wstream[p] : c->server_stream;
+        if (!own) {
+            HIP_TRY(c, hipEventRecord(c->ev_grad[p], c->wstream[p]));
+            HIP_TRY(c, hipStreamWaitEvent(as, c->ev_grad[p], 0));
+        }
+        if (c->version > 1) HIP_TRY(c, hipStreamWaitEvent(as, c->ev_apply, 0));
         for (int q = 0; q < c->K; ++q)
             if (c->pull_pending[q]) {
-                HIP_TRY(c, hipStreamWaitEvent(c->server_stream, c->ev_pull[q], 0));
+                if (c->wstream[q] != as) HIP_TRY(c, hipStreamWaitEvent(as, c->ev_pull[q], 0));
                 c->pull_pending[q] = 0;
             }
         int rc;
         if (fused)      // the worker's stream gets at the snapshot through ev_apply, like at any other pull
-            rc = dsspk_apply_pull(c->server_stream, c->params, grad_dev, pull_dst_dev, c->n_params, c->scale, c->stamps_dev,
+            rc = dsspk_apply_pull(as, c->params, grad_dev, pull_dst_dev, c->n_params, c->scale, c->stamps_dev,
                                   c->stamps_dev + 1 + p, c->version);
         else
-            rc = dsspk_apply(c->server_stream, c->params, grad_dev, c->n_params, c->scale, c->stamps_dev, c->version);
+            rc = dsspk_apply(as, c->params, grad_dev, c->n_params, c->scale, c->stamps_dev, c->version);
         if (rc) return fail(c, DSSP_EHIP, "apply kernel launch failed (rc " + std::to_string(rc) + ")");
-        HIP_TRY(c, hipEventRecord(c->ev_apply, c->server_stream));
-        if (fused) HIP_TRY(c, hipStreamWaitEvent(c->wstream[p], c->ev_apply, 0));
+        HIP_TRY(c, hipEventRecord(c->ev_apply, as));
+        if (fused && !own) HIP_TRY(c, hipStreamWaitEvent(c->wstream[p], c->ev_apply, 0));
     }
     *ok_out = ok ? 1 : 0;
     *n_released_out = n_rel;
@@ -392,7 +398,6 @@ extern "C" int dssp_destroy(dssp_ctx* c) {
             if (c->ev_pull[p]) (void)hipEventDestroy(c->ev_pull[p]);
             if (c->own_wstream[p] && c->wstream[p]) (void)hipStreamDestroy(c->wstream[p]);
         }
-        if (c->own_server_stream && c->server_stream) (void)hipStreamDestroy(c->server_stream);
         if (c->stamps_dev) (void)hipFree(c->stamps_dev);
     }
     delete c;

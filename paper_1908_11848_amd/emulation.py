@@ -13,13 +13,18 @@ from . import driver
 
 class Emulation:
     def __init__(self, model, K, s_L, r_max, lr, w0, batch=0, n_classes=0, xs=None, ys=None, grads=None,
-                 device="cuda:0", worker_streams=None):
+                 device="cuda:0", worker_streams=None, server_stream=False):
         """model: 'mlp' | 'alexnet_ds' | 'resnet<d>' | 'none'.
         w0: float32 initial weights.  xs[p][j] / ys[p][j]: pool of mini-batches of worker p
         (cycled); grads[p]: fixed gradient buffers for model 'none' (server stress).
         worker_streams: number of HIP streams the K workers are dealt onto (worker p -> stream p mod
-        that number; default one stream per worker).  Ordering between workers goes through the
-        library's events either way, so results do not depend on it."""
+        that number).  Default: one stream per hardware queue, each on a queue of its own (found with
+        dssp_stream_queues), since streams that share a queue run one after the other anyway and an
+        uneven spread of the workers over the queues costs throughput.  A given number of streams is
+        spread over the queues as evenly as they allow.  Ordering between workers goes through the
+        library's events either way, so results do not depend on it.
+        server_stream: give the server's applies a stream of their own instead of the pusher's (same results;
+        slower when that stream shares a hardware queue with a worker's)."""
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required")
         B.lib()
@@ -38,11 +43,12 @@ class Emulation:
             for p in range(K):
                 self.grad[p].copy_(torch.from_numpy(np.ascontiguousarray(grads[p], dtype=np.float32)))
         self.loss = torch.zeros(K, dtype=torch.float32, device=self.dev)
-        ns = K if not worker_streams else max(1, min(K, int(worker_streams)))
-        pool = [torch.cuda.Stream(device=self.dev) for _ in range(ns)]
-        self.streams = [pool[p % ns] for p in range(K)] + [torch.cuda.Stream(device=self.dev)]
+        lanes, self.hardware_queues = self._lanes(K, worker_streams)
+        self.streams = [lanes[p % len(lanes)] for p in range(K)]
         self.ctx = B.dssp_create(self.w, n, K, s_L, r_max, lr)
-        B.dssp_set_stream(self.ctx, -1, self.streams[K])
+        if server_stream:
+            self.streams.append(torch.cuda.Stream(device=self.dev))
+            B.dssp_set_stream(self.ctx, -1, self.streams[K])
         for p in range(K):
             B.dssp_set_stream(self.ctx, p, self.streams[p])
         self.ws = None
@@ -55,6 +61,21 @@ class Emulation:
         torch.cuda.synchronize()
         self.on_step = None            # test hook: called after a worker step was enqueued
         self.before_step = None        # test hook: called after the pull, before the step is enqueued
+
+    _spread = {}        # device index -> (streams ordered so that any prefix is spread evenly over the queues, queues)
+
+    def _lanes(self, K, worker_streams):
+        """Streams for the workers, out of torch's pool.  The pool lives as long as the process, so it is probed once."""
+        key = self.dev.index or 0
+        if key not in Emulation._spread:
+            cand = [torch.cuda.Stream(device=self.dev) for _ in range(16)]
+            queue, nq = B.dssp_stream_queues(cand)
+            by_queue = [[s for s, q in zip(cand, queue) if q == g] for g in range(nq)]
+            order = [row[depth] for depth in range(len(cand)) for row in by_queue if depth < len(row)]
+            Emulation._spread[key] = (order, nq)
+        order, nq = Emulation._spread[key]
+        want = min(K, nq) if not worker_streams else max(1, min(K, len(order), int(worker_streams)))
+        return order[:want], nq
 
     # ------------------------------------------------------------------ pieces
     def step(self, p, n):

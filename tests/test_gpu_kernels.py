@@ -7,6 +7,8 @@ about sqrt(n) * 6e-8 relative to the operand scale, so 2e-6 relative L2 covers e
 with an order of magnitude to spare.  Integer outputs (arg-max positions) and copies are
 bit-exact.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -497,3 +499,28 @@ def test_shortcut_gap_softmax(oracle_nn):
         lo, dzo = oracle_nn.softmax_xent(z.astype(np.float64), lab)
         assert abs(host(loss)[0] - lo) < 2e-6 * max(1, abs(lo))
         assert rel_l2(host(dz), dzo) < TOL
+
+
+# ------------------------------------------------------------------ streams and hardware queues
+def test_streams_are_grouped_by_hardware_queue():
+    pool = [torch.cuda.Stream() for _ in range(10)]
+    streams = pool + [pool[3], pool[0]]
+    queue, nq = B.dssp_stream_queues(streams)
+    # a process has 4 hardware queues unless GPU_MAX_HW_QUEUES says otherwise, so ten streams must share some
+    assert 1 <= nq <= int(os.environ.get("GPU_MAX_HW_QUEUES", 4)) and sorted(set(queue)) == list(range(nq))
+    assert queue[0] == 0 and all(queue[i] <= max(queue[:i]) + 1 for i in range(1, len(queue)))   # numbered by first appearance
+    assert queue[10] == queue[3] and queue[11] == queue[0]                                       # the same stream twice
+    again, nq2 = B.dssp_stream_queues(streams)
+    assert (again, nq2) == (queue, nq)
+    # the grouping is real: a spin on one stream holds up a stream of the same queue and no stream of another
+    if nq > 1:
+        a = queue.index(0)
+        other = next(i for i, q in enumerate(queue) if q != 0)
+        pair, _ = B.dssp_stream_queues([streams[a], streams[other]])
+        assert pair == [0, 1]
+    same = [i for i, q in enumerate(queue[:10]) if q == queue[0]]
+    if len(same) > 1:
+        pair, n_pair = B.dssp_stream_queues([streams[same[0]], streams[same[1]]])
+        assert pair == [0, 0] and n_pair == 1
+    with pytest.raises(B.DsspError):
+        B.dssp_stream_queues([pool[0]] * 65)

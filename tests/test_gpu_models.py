@@ -186,6 +186,12 @@ def test_resnet8_step_and_50_updates(oracle_nn):
     log, _ = em.run(d, total=50)
     assert log == out["log"] and np.array_equal(em.weights(), w_gpu)
     em.close()
+    # the applies on a stream of the server's own instead of the pushers': same schedule, same bits
+    for fused in (False, True):
+        em = Emulation(model, K, 3, 12, 0.05, w0, batch, 100, xs, ys, server_stream=True)
+        log, _ = em.run(d, total=50, fused_pull=fused)
+        assert log == out["log"] and np.array_equal(em.weights(), w_gpu)
+        em.close()
     em = Emulation(model, K, 3, 12, 0.05, w0, batch, 100, xs, ys)
     for p in range(K):
         B.dssp_pull(em.ctx, p, em.w_local[p])
@@ -268,14 +274,16 @@ def test_server_stress_config5(oracle_nn):
     for p in range(K):
         if stamps[1 + p] == 50:
             assert np.array_equal(em.w_local[p].cpu().numpy(), w_gpu)
-    # (a') the same 50 pushes with the pusher's pull folded into the apply kernel: same log, same bits, same stamps
-    em2 = Emulation("none", K, 3, 15, lr, w0, grads=g)
-    log2, _ = em2.run(d, total=50, fused_pull=True)
-    assert log2 == log and np.array_equal(em2.weights(), w_gpu)
-    assert B.dssp_device_stamps(em2.ctx, K) == stamps
-    for p in range(K):
-        assert np.array_equal(em2.w_local[p].cpu().numpy(), em.w_local[p].cpu().numpy())
-    em2.close()
+    # (a') the same 50 pushes with the pusher's pull folded into the apply kernel, and with the applies on a
+    # stream of the server's own: same log, same bits, same stamps
+    for fused, server_stream in ((True, False), (False, True), (True, True)):
+        em2 = Emulation("none", K, 3, 15, lr, w0, grads=g, server_stream=server_stream)
+        log2, _ = em2.run(d, total=50, fused_pull=fused)
+        assert log2 == log and np.array_equal(em2.weights(), w_gpu)
+        assert B.dssp_device_stamps(em2.ctx, K) == stamps
+        for p in range(K):
+            assert np.array_equal(em2.w_local[p].cpu().numpy(), em.w_local[p].cpu().numpy())
+        em2.close()
     em.close()
     # (b) all 10k pushes: schedule bit-exact, weights against the closed form w0 - scale * sum_p count_p g_p
     em = Emulation("none", K, 3, 15, lr, w0, grads=g)
