@@ -1,5 +1,5 @@
 /* libdssp: Dynamic Stale Synchronous Parallel parameter-server training, hot path,
- * K virtual workers on K HIP streams of one MI355X (gfx950).
+ * K virtual workers on HIP streams of one MI355X (gfx950).
  *
  * The calls follow the paper's problem statement (Sec. III-A) and Algorithm 1:
  *   worker part : wait for OK, pull w, replace local weights, gradient of the
@@ -125,8 +125,8 @@ int dssp_worker_step(dssp_ctx* ctx, int worker, const float* x_dev, const int32_
                      const float* w_local_dev, float* grad_dev, float* loss_dev);
 
 /* Alg. 1, worker step 5 + server part, Alg. 2: the push of `worker` reaches the server at
- * virtual time t_push_ticks.  Counts it, enqueues the apply on the server stream behind the
- * worker's gradient computation, then decides.
+ * virtual time t_push_ticks.  Counts it, decides, and enqueues the apply behind the worker's
+ * gradient computation (on the worker's stream, or on the server's if one was set).
  *   grad_dev         n_params floats; must stay untouched until the worker's next pull has run
  *                    (the next dssp_worker_step of that worker may overwrite it)
  *   ok_out           1 = OK now, 0 = the worker waits until a later push releases it

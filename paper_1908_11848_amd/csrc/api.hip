@@ -1,5 +1,5 @@
 // C ABI of libdssp: context, the server's decision logic (Alg. 1 server part, Alg. 2) on the
-// host, and the stream / event ordering between the server stream and the K worker streams.
+// host, and the stream / event ordering between the applies and the K workers' streams.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
