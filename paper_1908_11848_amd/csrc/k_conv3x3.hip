@@ -37,10 +37,15 @@ struct Cfg {
     static constexpr int KC = C / 16;              // 16-wide chunks of the reduction channel
     static constexpr int SS = 8 * CN;              // per-wavefront column sums (batch-norm records, two components)
     static constexpr int PS = THREADS + 2 * C;     // merge of the input's batch-norm records: tree + (mean, invstd)
+    // Winograd F(2x2, 3x3) for the matrix-core part: a wavefront's 16 "pixels" are 16 tiles of 2x2 outputs, the
+    // nine taps become 16 element-wise products of transformed 4x4 patches and transformed filters, 4/9 of the
+    // matrix-core work.  One run of 16 tiles per wavefront.
+    static constexpr bool WINO = (C == 16 || C == 32);
     static constexpr size_t LDS_BYTES = (size_t)(XS + SS + PS) * sizeof(float);
     static constexpr size_t LDS_BYTES_WG = LDS_BYTES + (size_t)XS * sizeof(float);   // + the x halo tile of the fused d-filter
     static_assert(WAVES_N == 1 || WAVES_N == 2 || WAVES_N == 4, "one 16-channel tile per wavefront");
     static_assert(RUNS % WAVES_M == 0 && WM >= 1, "band must give every wavefront at least one run");
+    static_assert(!WINO || (WM == 4 && (R / 2) * (HW / 2) == 16 * WAVES_M), "Winograd: one run of 16 tiles, 16 outputs per lane");
 };
 
 // Normalisation applied to the input while it is loaded (PRE != 0): the kernel then computes
@@ -99,8 +104,13 @@ struct WgradFused {
 
 // add and dst may be the same buffer (every element is read and written by the same lane); with PRE == 3
 // dst must differ from src, whose halo rows other workgroups still read.
+// Registers: with the Winograd form the compiler would keep all 16 accumulator tiles in flight and the kernel
+// at 2-3 wavefronts per SIMD; told how many should fit, it orders the work row by row instead (no spills).
+template <int C, bool TRANSPOSED, bool WG>
+constexpr int min_waves() { return C == 16 ? (WG ? 2 : TRANSPOSED ? 3 : 4) : C == 32 ? 2 : 1; }
+
 template <int C, int HW, int R, int NSPLIT, bool TRANSPOSED, int PRE, bool POST = false, bool WG = false>
-__global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_waves<C, TRANSPOSED, WG>()))) void conv3x3_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
                                                           const float* add, float* dst,
                                                           float* __restrict__ bn_partial, PreBn pre, PostBn post, BwdBn bwd,
                                                           int conv_blocks, jobs::ReduceJob rj, WgradFused wg) {
@@ -228,8 +238,80 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
         }
     __syncthreads();
 
-    // ---- 9 taps x C/16 k-chunks: A from LDS, B from registers
     floatx4 acc[K::WM];
+    // band-local pixel (row-major) of accumulator element (wm, v)
+    auto pixel = [&](int wm, int v) {
+        if constexpr (K::WINO) {       // tile 4q + v of the wavefront's run, output (wm / 2, wm % 2) of its 2x2
+            const int g = wave_m * 16 + 4 * q + v;
+            return (2 * (g / (HW / 2)) + (wm >> 1)) * HW + 2 * (g % (HW / 2)) + (wm & 1);
+        } else {                       // run wm of the wavefront, pixel 4q + v of the run
+            return (wave_m * K::WM + wm) * 16 + 4 * q + v;
+        }
+    };
+    if constexpr (K::WINO) {
+        // ---- Winograd F(2x2, 3x3), Y = A^T [ (G g G^T) .* (B^T d B) ] A per tile and channel pair, the products
+        //      summed over the input channels by the matrix cores: for each of the 16 positions of the transformed
+        //      4x4 patch, M[tile][co] += V[tile][k] U[k][co].  A lane transforms the patch of tile l16 (channels
+        //      16 kc + 4q ..) and the filter of output channel `co` (same channels), both element-wise on float4.
+        constexpr int TXN = HW / 2;
+        const int g = wave_m * 16 + l16;
+        const int base = (2 * (g / TXN) * K::TW + 2 * (g % TXN)) * K::LDC + 4 * q;
+        // Row a of the transformed patch at a time (4 of the 16 positions), so that only its four accumulators,
+        // its four U and V values and the running A^T M sums are live: s0 = M0 + M1 + M2, s1 = M1 - M2 - M3.
+        floatx4 s0[4], s1[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            floatx4 m[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) m[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kc = 0; kc < K::KC; ++kc) {
+                float4 U[4];           // row a of G g G^T, G = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1]
+                {
+                    float4 u[3];
+#pragma unroll
+                    for (int j = 0; j < 3; ++j) {
+                        const float4 g0 = bf[j][kc], g1 = bf[3 + j][kc], g2 = bf[6 + j][kc];
+                        u[j] = a == 0 ? g0 : a == 3 ? g2 : a == 1 ? (g0 + g2) * 0.5f + g1 * 0.5f : (g0 + g2) * 0.5f - g1 * 0.5f;
+                    }
+                    const float4 e = (u[0] + u[2]) * 0.5f, o = u[1] * 0.5f;
+                    U[0] = u[0]; U[1] = e + o; U[2] = e - o; U[3] = u[2];
+                }
+                float4 V[4];           // row a of B^T d B, B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1]
+                {
+                    constexpr int RA[4] = {0, 1, 2, 1}, RB[4] = {2, 2, 1, 3};      // t[a] = +-d[RA] +- d[RB]
+                    float4 t[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float4 da = *reinterpret_cast<const float4*>(&Xs[base + (RA[a] * K::TW + c) * K::LDC + 16 * kc]);
+                        const float4 db = *reinterpret_cast<const float4*>(&Xs[base + (RB[a] * K::TW + c) * K::LDC + 16 * kc]);
+                        t[c] = a == 1 ? da + db : da - db;
+                    }
+                    V[0] = t[0] - t[2]; V[1] = t[1] + t[2]; V[2] = t[2] - t[1]; V[3] = t[1] - t[3];
+                }
+#pragma unroll
+                for (int b = 0; b < 4; ++b) m[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[b].x, U[b].x, m[b], 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) m[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[b].y, U[b].y, m[b], 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) m[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[b].z, U[b].z, m[b], 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) m[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[b].w, U[b].w, m[b], 0, 0, 0);
+            }
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (a == 0) s0[b] = m[b];
+                if (a == 1) { s0[b] += m[b]; s1[b] = m[b]; }
+                if (a == 2) { s0[b] += m[b]; s1[b] -= m[b]; }
+                if (a == 3) s1[b] -= m[b];
+            }
+        }
+        mma::drain();
+        // (A^T M) A, A^T = [1 1 1 0; 0 1 -1 -1]: element v of every accumulator belongs to tile 4q + v
+        acc[0] = s0[0] + s0[1] + s0[2]; acc[1] = s0[1] - s0[2] - s0[3];
+        acc[2] = s1[0] + s1[1] + s1[2]; acc[3] = s1[1] - s1[2] - s1[3];
+    } else {
+    // ---- 9 taps x C/16 k-chunks: A from LDS, B from registers
 #pragma unroll
     for (int wm = 0; wm < K::WM; ++wm) acc[wm] = floatx4{0.f, 0.f, 0.f, 0.f};
     int pix_off[K::WM];                             // LDS offset of this lane's pixel for tap (0,0)
@@ -259,9 +341,10 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
             for (int wm = 0; wm < K::WM; ++wm) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].w, b.w, acc[wm], 0, 0, 0);
         }
     }
+    }
 
     mma::drain();
-    // ---- store: lane holds rows 4q..4q+3 (pixels of the run) of column l16
+    // ---- store: lane holds the elements acc[wm][v] of pixels pixel(wm, v), all of output channel co
     float sum_dz = 0.f, sum_dzx = 0.f, mu_c = 0.f, is_c = 0.f;
     if constexpr (POST) {
         mu_c = post.stats[co];
@@ -270,7 +353,7 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
     // all loads of the epilogue first (dst may alias add, so the compiler cannot move them across the stores itself)
     float addv[K::WM][4], maskv[POST ? K::WM : 1][4], xcv[POST ? K::WM : 1][4];
     auto out_off = [&](int wm, int v) {
-        const int p = (wave_m * K::WM + wm) * 16 + 4 * q + v;
+        const int p = pixel(wm, v);
         return (((long)n * HW + r_base + p / HW) * HW + p % HW) * C + co;
     };
 #pragma unroll
@@ -281,7 +364,7 @@ __global__ __launch_bounds__(THREADS) void conv3x3_kernel(const float* __restric
             addv[wm][v] = add ? add[off] : 0.f;
             if constexpr (POST) {
                 if constexpr (WG) {     // the mask source is the convolution's input, whose tile is in LDS
-                    const int p = (wave_m * K::WM + wm) * 16 + 4 * q + v;
+                    const int p = pixel(wm, v);
                     maskv[wm][v] = Xs2[((p / HW + 1) * K::TW + (p % HW + 1)) * K::LDC + co];
                 } else {
                     maskv[wm][v] = post.mask_src[off];
