@@ -3,15 +3,21 @@
 //
 // A workgroup owns a band of R output rows of one image (the whole 8x8 image in the last
 // stage) and CN of the C output channels.  It loads the (R+2) x (HW+2) x C input halo tile
-// (zero borders) into LDS once; all nine taps are then served from LDS, so every input element
+// (zero borders) into LDS once; everything else is served from LDS, so every input element
 // is read from memory once per band instead of nine times.  The filter never passes through
 // LDS: a wavefront owns ONE tile of 16 output channels and keeps that tile's 9 x C filter
 // values in registers (9 * C / 16 float4 per lane, fetched straight from the cached filter
 // while the halo tile is still in flight).  LDS therefore holds the halo tile only (about
 // 27 KB in every stage), which lets workgroups of several kernels share a compute unit.
-// Matrix-core tiles are 16 pixels (a run along the image row; two 8-pixel rows in the last
-// stage) x 16 output channels, v_mfma_f32_16x16x4_f32, with the k-permutation of mma.hpp: both
-// operands are k-contiguous per lane, so one 16-byte LDS read per run feeds four MFMAs.
+//
+// The arithmetic is Winograd's minimal filtering F(2x2, 3x3) (Lavin & Gray, "Fast Algorithms for
+// Convolutional Neural Networks"): per 2x2 output tile and channel pair 16 multiplications instead of 36,
+// Y = A^T [ (G g G^T) .* (B^T d B) ] A with the element-wise products summed over the input channels - which
+// is a matrix product per position of the transformed 4x4 patch, M_xi[tile][co] = sum_k V_xi[tile][k] U_xi[k][co].
+// Those 16 products run on the matrix cores: v_mfma_f32_16x16x4_f32, 16 tiles x 16 output channels per wavefront,
+// with the k-permutation of mma.hpp (both operands k-contiguous per lane: one float4 feeds four MFMAs).  Patch and
+// filter transforms are float4 additions in registers (no multiplications but the halvings of G), so the matrix
+// cores do 4/9 of the direct form's work; in fp32 the result differs from the direct form by a few ulps.
 //
 // Gradient w.r.t. the input of such a convolution is the same operation on dy with the filter
 // taps reversed and its two channel indices swapped; only the filter fetch differs.
@@ -30,22 +36,25 @@ struct Cfg {
     static constexpr int LDC = C + 4;              // pitch of one pixel in LDS (floats)
     static constexpr int TW = HW + 2;              // halo tile width
     static constexpr int XS = (R + 2) * TW * LDC;  // floats
-    static constexpr int RUNS = R * HW / 16;       // 16-pixel runs in the band
+    static constexpr int RUNS = R * HW / 16;       // output pixels of the band / 16
     static constexpr int WAVES_N = CN / 16;        // wavefronts side by side over the output channels
     static constexpr int WAVES_M = 4 / WAVES_N;    // ... and over the runs
-    static constexpr int WM = RUNS / WAVES_M;      // runs per wavefront
+    static constexpr int WM = RUNS / WAVES_M;      // accumulator tiles (16 pixels x 16 channels) a wavefront finishes
     static constexpr int KC = C / 16;              // 16-wide chunks of the reduction channel
     static constexpr int SS = 8 * CN;              // per-wavefront column sums (batch-norm records, two components)
     static constexpr int PS = THREADS + 2 * C;     // merge of the input's batch-norm records: tree + (mean, invstd)
-    // Winograd F(2x2, 3x3) for the matrix-core part: a wavefront's 16 "pixels" are 16 tiles of 2x2 outputs, the
-    // nine taps become 16 element-wise products of transformed 4x4 patches and transformed filters, 4/9 of the
-    // matrix-core work.  One run of 16 tiles per wavefront.
-    static constexpr bool WINO = (C == 16 || C == 32);
+    // A run is 16 tiles of 2x2 outputs; every wavefront works on one run.  If the band has fewer runs than
+    // WAVES_M (last stage: 16 tiles per image), KS wavefronts share a run and split the input channels; they swap
+    // halves of their partial results through LDS and each finishes its half.
+    static constexpr int WRUNS = (R / 2) * (HW / 2) / 16;      // runs per band
+    static constexpr int KS = WAVES_M / WRUNS;                 // wavefronts per run, each with 1/KS of the channels
+    static constexpr int KCW = KC / KS;                        // k-chunks per wavefront
     static constexpr size_t LDS_BYTES = (size_t)(XS + SS + PS) * sizeof(float);
     static constexpr size_t LDS_BYTES_WG = LDS_BYTES + (size_t)XS * sizeof(float);   // + the x halo tile of the fused d-filter
     static_assert(WAVES_N == 1 || WAVES_N == 2 || WAVES_N == 4, "one 16-channel tile per wavefront");
     static_assert(RUNS % WAVES_M == 0 && WM >= 1, "band must give every wavefront at least one run");
-    static_assert(!WINO || (WM == 4 && (R / 2) * (HW / 2) == 16 * WAVES_M), "Winograd: one run of 16 tiles, 16 outputs per lane");
+    static_assert(WRUNS * KS == WAVES_M && (KS == 1 || KS == 2) && WM * KS == 4 && KCW * KS == KC,
+                  "one run of 16 tiles per wavefront, 16 / KS outputs per lane");
 };
 
 // Normalisation applied to the input while it is loaded (PRE != 0): the kernel then computes
@@ -224,15 +233,17 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_wav
     // ---- filter values of this wavefront's 16 output channels, B[k][co] with k = 16 kc + 4 q + {0..3}:
     //      forward : w[tap][k][co]           (four loads, C floats apart)
     //      d-input : w[8 - tap][co][k]       (one 16-byte load, taps reversed)
-    float4 bf[9][K::KC];
+    const int wrun = wave_m / K::KS, ks = wave_m % K::KS;      // this wavefront's run and share of the channels
+    const int k0 = 16 * K::KCW * ks + 4 * q;                   // its first reduction channel
+    float4 bf[9][K::KCW];
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
-        for (int kc = 0; kc < K::KC; ++kc) {
+        for (int kc = 0; kc < K::KCW; ++kc) {
             if constexpr (TRANSPOSED) {
-                bf[tap][kc] = *reinterpret_cast<const float4*>(wgt + ((long)(8 - tap) * C + co) * C + 16 * kc + 4 * q);
+                bf[tap][kc] = *reinterpret_cast<const float4*>(wgt + ((long)(8 - tap) * C + co) * C + k0 + 16 * kc);
             } else {
-                const float* wp = wgt + ((long)tap * C + 16 * kc + 4 * q) * C + co;
+                const float* wp = wgt + ((long)tap * C + k0 + 16 * kc) * C + co;
                 bf[tap][kc] = make_float4(wp[0], wp[C], wp[2 * C], wp[3 * C]);
             }
         }
@@ -240,22 +251,18 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_wav
 
     floatx4 acc[K::WM];
     // band-local pixel (row-major) of accumulator element (wm, v)
-    auto pixel = [&](int wm, int v) {
-        if constexpr (K::WINO) {       // tile 4q + v of the wavefront's run, output (wm / 2, wm % 2) of its 2x2
-            const int g = wave_m * 16 + 4 * q + v;
-            return (2 * (g / (HW / 2)) + (wm >> 1)) * HW + 2 * (g % (HW / 2)) + (wm & 1);
-        } else {                       // run wm of the wavefront, pixel 4q + v of the run
-            return (wave_m * K::WM + wm) * 16 + 4 * q + v;
-        }
+    auto pixel = [&](int wm, int v) {   // tile 4q + v of the wavefront's run, output (e / 2, e % 2) of its 2x2
+        const int g = wrun * 16 + 4 * q + v, e = ks * K::WM + wm;
+        return (2 * (g / (HW / 2)) + (e >> 1)) * HW + 2 * (g % (HW / 2)) + (e & 1);
     };
-    if constexpr (K::WINO) {
+    {
         // ---- Winograd F(2x2, 3x3), Y = A^T [ (G g G^T) .* (B^T d B) ] A per tile and channel pair, the products
         //      summed over the input channels by the matrix cores: for each of the 16 positions of the transformed
         //      4x4 patch, M[tile][co] += V[tile][k] U[k][co].  A lane transforms the patch of tile l16 (channels
         //      16 kc + 4q ..) and the filter of output channel `co` (same channels), both element-wise on float4.
         constexpr int TXN = HW / 2;
-        const int g = wave_m * 16 + l16;
-        const int base = (2 * (g / TXN) * K::TW + 2 * (g % TXN)) * K::LDC + 4 * q;
+        const int g = wrun * 16 + l16;
+        const int base = (2 * (g / TXN) * K::TW + 2 * (g % TXN)) * K::LDC + k0;
         // Row a of the transformed patch at a time (4 of the 16 positions), so that only its four accumulators,
         // its four U and V values and the running A^T M sums are live: s0 = M0 + M1 + M2, s1 = M1 - M2 - M3.
         floatx4 s0[4], s1[4];
@@ -265,7 +272,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_wav
 #pragma unroll
             for (int b = 0; b < 4; ++b) m[b] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kc = 0; kc < K::KC; ++kc) {
+            for (int kc = 0; kc < K::KCW; ++kc) {
                 float4 U[4];           // row a of G g G^T, G = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1]
                 {
                     float4 u[3];
@@ -308,39 +315,32 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_wav
         }
         mma::drain();
         // (A^T M) A, A^T = [1 1 1 0; 0 1 -1 -1]: element v of every accumulator belongs to tile 4q + v
-        acc[0] = s0[0] + s0[1] + s0[2]; acc[1] = s0[1] - s0[2] - s0[3];
-        acc[2] = s1[0] + s1[1] + s1[2]; acc[3] = s1[1] - s1[2] - s1[3];
-    } else {
-    // ---- 9 taps x C/16 k-chunks: A from LDS, B from registers
+        floatx4 y[4];
+        y[0] = s0[0] + s0[1] + s0[2]; y[1] = s0[1] - s0[2] - s0[3];
+        y[2] = s1[0] + s1[1] + s1[2]; y[3] = s1[1] - s1[2] - s1[3];
+        if constexpr (K::KS == 1) {
 #pragma unroll
-    for (int wm = 0; wm < K::WM; ++wm) acc[wm] = floatx4{0.f, 0.f, 0.f, 0.f};
-    int pix_off[K::WM];                             // LDS offset of this lane's pixel for tap (0,0)
+            for (int wm = 0; wm < 4; ++wm) acc[wm] = y[wm];
+        } else {
+            // the two wavefronts of a run hold partial sums over their halves of the input channels: each hands
+            // the other the two accumulators it will not finish and adds what it receives (first half + second half)
+            __syncthreads();                               // every wavefront has read the tile for the last time
+            float* Ex = lds;                               // [wavefront][2][4][64]
 #pragma unroll
-    for (int wm = 0; wm < K::WM; ++wm) {
-        const int run = wave_m * K::WM + wm;
-        const int p = run * 16 + l16;               // pixel index inside the band, row-major
-        pix_off[wm] = ((p / HW) * K::TW + (p % HW)) * K::LDC + 4 * q;
-    }
+            for (int wm = 0; wm < 2; ++wm)
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) {
-        const int toff = ((tap / 3) * K::TW + (tap % 3)) * K::LDC;
+                for (int v = 0; v < 4; ++v) Ex[((wave * 2 + wm) * 4 + v) * 64 + lane] = ks == 0 ? y[2 + wm][v] : y[wm][v];
+            __syncthreads();
+            const int partner = (wave_m ^ 1) * K::WAVES_N + wave_n;
 #pragma unroll
-        for (int kc = 0; kc < K::KC; ++kc) {
-            float4 a[K::WM];
+            for (int wm = 0; wm < 2; ++wm)
 #pragma unroll
-            for (int wm = 0; wm < K::WM; ++wm)
-                a[wm] = *reinterpret_cast<const float4*>(&Xs[pix_off[wm] + toff + 16 * kc]);
-            const float4 b = bf[tap][kc];
-#pragma unroll
-            for (int wm = 0; wm < K::WM; ++wm) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].x, b.x, acc[wm], 0, 0, 0);
-#pragma unroll
-            for (int wm = 0; wm < K::WM; ++wm) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].y, b.y, acc[wm], 0, 0, 0);
-#pragma unroll
-            for (int wm = 0; wm < K::WM; ++wm) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].z, b.z, acc[wm], 0, 0, 0);
-#pragma unroll
-            for (int wm = 0; wm < K::WM; ++wm) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[wm].w, b.w, acc[wm], 0, 0, 0);
+                for (int v = 0; v < 4; ++v) {
+                    const float other = Ex[((partner * 2 + wm) * 4 + v) * 64 + lane];
+                    const float own = ks == 0 ? y[wm][v] : y[2 + wm][v];
+                    acc[wm][v] = ks == 0 ? own + other : other + own;
+                }
         }
-    }
     }
 
     mma::drain();
