@@ -374,33 +374,79 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_wav
         }
     if constexpr (WG) {
         // ---- d-filter of the same layer from the two LDS tiles, while the epilogue's operands are in flight:
-        //      A[ci][pixel] = x[pixel + tap][ci] (Xs2), B[pixel][co] = dx[pixel][co] (interior of Xs).
-        //      C = 16: one 16x16 tile per tap, the four wavefronts split the pixel chunks and are summed in a
-        //      fixed order; C = 32: wavefront w owns tile (w / 2, w % 2) and walks all chunks.
+        //      dw[tap][ci][co] = sum over pixels x[pixel + tap][ci] dx[pixel][co], again by minimal filtering, now
+        //      F(3x3, 2x2): per 2x2 tile of dx and its 4x4 patch of x, dw += A^T [ (B^T x B) .* (G dx G^T) ] A with
+        //      B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 -1 0 1], G = [1 0; .5 .5; .5 -.5; 0 1], A^T = [1 1 1 0; 0 1 -1 0; 0 1 1 1].
+        //      The sum over tiles is taken in the transformed domain by the matrix cores, M_xi[ci][co] += sum over
+        //      tiles XT_xi[ci][tile] DT_xi[tile][co] (16 products instead of 36 per tile), and A^T M A is applied once
+        //      at the end.  A lane transforms, as scalars, the patches (channel 16 cit + l16) and dx tiles (channel
+        //      16 cot + l16) of the four tiles it feeds to the four MFMAs of a run.
+        //      C = 16: one 16x16 tile of (ci, co), the four wavefronts take one run each and are summed in a fixed
+        //      order; C = 32: wavefront w owns tile (w / 2, w % 2) and walks both runs.
         constexpr bool SPLIT_K = (C == 16);
-        constexpr int CHUNKS = R * HW / 16;
+        constexpr int TXN = HW / 2;
         const int cit = SPLIT_K ? 0 : wave >> 1, cot = SPLIT_K ? 0 : wave & 1;
-        floatx4 dwa[9];
+        floatx4 M[16];
 #pragma unroll
-        for (int t = 0; t < 9; ++t) dwa[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-        for (int c = SPLIT_K ? wave : 0; c < CHUNKS; c += SPLIT_K ? 4 : 1) {
-            float b[4];
-            int xo[4];
+        for (int xi = 0; xi < 16; ++xi) M[xi] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int run = SPLIT_K ? wave : 0; run < K::WRUNS; run += SPLIT_K ? 4 : 1) {
 #pragma unroll
             for (int s_ = 0; s_ < 4; ++s_) {
-                const int p = 16 * c + 4 * q + s_;
-                b[s_] = Xs[((p / HW + 1) * K::TW + (p % HW + 1)) * K::LDC + 16 * cot + l16];
-                xo[s_] = ((p / HW) * K::TW + (p % HW)) * K::LDC + 16 * cit + l16;
-            }
+                const int g = run * 16 + 4 * q + s_;
+                const int o = (2 * (g / TXN) * K::TW + 2 * (g % TXN)) * K::LDC;      // the patch's corner in both halo tiles
+                float XT[16], DT[16];
+                {
+                    float t[4][4];
 #pragma unroll
-            for (int t = 0; t < 9; ++t) {
-                const int toff = ((t / 3) * K::TW + (t % 3)) * K::LDC;
+                    for (int c = 0; c < 4; ++c) {
+                        float x[4];
 #pragma unroll
-                for (int s_ = 0; s_ < 4; ++s_)
-                    dwa[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Xs2[xo[s_] + toff], b[s_], dwa[t], 0, 0, 0);
+                        for (int r = 0; r < 4; ++r) x[r] = Xs2[o + (r * K::TW + c) * K::LDC + 16 * cit + l16];
+                        t[0][c] = x[0] - x[2]; t[1][c] = x[1] + x[2]; t[2][c] = x[2] - x[1]; t[3][c] = x[3] - x[1];
+                    }
+#pragma unroll
+                    for (int a_ = 0; a_ < 4; ++a_) {
+                        XT[4 * a_] = t[a_][0] - t[a_][2]; XT[4 * a_ + 1] = t[a_][1] + t[a_][2];
+                        XT[4 * a_ + 2] = t[a_][2] - t[a_][1]; XT[4 * a_ + 3] = t[a_][3] - t[a_][1];
+                    }
+                }
+                {
+                    float d[2][2], u[4][2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) d[i][j] = Xs[o + ((i + 1) * K::TW + j + 1) * K::LDC + 16 * cot + l16];
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        u[0][j] = d[0][j]; u[1][j] = 0.5f * (d[0][j] + d[1][j]); u[2][j] = 0.5f * (d[0][j] - d[1][j]); u[3][j] = d[1][j];
+                    }
+#pragma unroll
+                    for (int a_ = 0; a_ < 4; ++a_) {
+                        DT[4 * a_] = u[a_][0]; DT[4 * a_ + 1] = 0.5f * (u[a_][0] + u[a_][1]);
+                        DT[4 * a_ + 2] = 0.5f * (u[a_][0] - u[a_][1]); DT[4 * a_ + 3] = u[a_][1];
+                    }
+                }
+#pragma unroll
+                for (int xi = 0; xi < 16; ++xi) M[xi] = __builtin_amdgcn_mfma_f32_16x16x4f32(XT[xi], DT[xi], M[xi], 0, 0, 0);
             }
         }
         mma::drain();
+        floatx4 dwa[9];
+        {
+            floatx4 S[3][4];
+#pragma unroll
+            for (int b_ = 0; b_ < 4; ++b_) {
+                S[0][b_] = M[b_] + M[4 + b_] + M[8 + b_];
+                S[1][b_] = M[4 + b_] - M[8 + b_];
+                S[2][b_] = M[4 + b_] + M[8 + b_] + M[12 + b_];
+            }
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                dwa[3 * r] = S[r][0] + S[r][1] + S[r][2];
+                dwa[3 * r + 1] = S[r][1] - S[r][2];
+                dwa[3 * r + 2] = S[r][1] + S[r][2] + S[r][3];
+            }
+        }
         float* pout = wg.partial + (long)blockIdx.x * 9 * C * C;
         if constexpr (SPLIT_K) {
             static_assert(!SPLIT_K || 4 * 9 * C * C <= 2 * K::XS + K::SS + K::PS, "room for the four partial sums");

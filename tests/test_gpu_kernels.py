@@ -161,6 +161,32 @@ def test_conv_forward_dgrad_wgrad(oracle_nn, case):
         assert rel_l2(host(dx), dxo + x64) < TOL              # with the shortcut's gradient added in the epilogue
 
 
+@pytest.mark.parametrize("N,H,C", [(3, 32, 16), (5, 16, 32), (4, 8, 64)])
+def test_minimal_filtering_on_inputs_with_a_large_common_offset(oracle_nn, N, H, C):
+    """The 3x3 kernels form differences of neighbouring inputs before they multiply (Winograd's patch transform), so
+    their rounding error scales with the magnitude of the inputs, not of the result.  Post-ReLU activations are all
+    positive; here the inputs sit at 8 +- 1 and every output channel's filter sums to zero, so the offset cancels
+    in the result, which is several times smaller than the inputs: the error, relative to the result, must stay at
+    the fp32 level all the same."""
+    g = np.random.default_rng(1000 * C + N)
+    x = (8.0 + g.standard_normal((N, H, H, C))).astype(np.float32)
+    w = g.standard_normal((3, 3, C, C)) * (2.0 / (9 * C)) ** 0.5
+    wf = (w - w.mean(axis=(0, 1, 2), keepdims=True)).astype(np.float32)      # forward: zero sum per output channel
+    wb = (w - w.mean(axis=(0, 1, 3), keepdims=True)).astype(np.float32)      # d-input: zero sum per input channel
+    dy = (8.0 + g.standard_normal((N, H, H, C))).astype(np.float32)
+    X, WF, WB, DY = dev(x), dev(wf), dev(wb), dev(dy)
+    st, L = stream_ptr(), B.lib()
+    y, dx = empty((N, H, H, C)), empty((N, H, H, C))
+    rc(L.dsspk_conv_fwd(st, X.data_ptr(), WF.data_ptr(), None, y.data_ptr(), N, H, H, C, C, 3, 3, 1, 1, 0, None))
+    rc(L.dsspk_conv_bwd_data(st, DY.data_ptr(), WB.data_ptr(), None, dx.data_ptr(), N, H, H, C, C, 3, 3, 1, 1))
+    x64, dy64 = x.astype(np.float64), dy.astype(np.float64)
+    yo = oracle_nn.conv2d_fwd(x64, wf.astype(np.float64), None, 1, 1)
+    dxo, _, _ = oracle_nn.conv2d_bwd(x64, wb.astype(np.float64), dy64, 1, 1, False, need_dx=True)
+    e_y, e_dx = rel_l2(host(y), yo), rel_l2(host(dx), dxo)
+    print("offset inputs %dx%dx%d: forward %.2e, d-input %.2e; interior |y| rms %.2f" % (H, H, C, e_y, e_dx, np.sqrt(np.mean(yo[:, 1:-1, 1:-1] ** 2))))
+    assert e_y < TOL and e_dx < TOL
+
+
 @pytest.mark.parametrize("N,H,C", [(3, 32, 16), (5, 16, 32), (4, 8, 64), (128, 32, 16), (128, 8, 64)])
 def test_conv_emits_batchnorm_statistics(oracle_nn, N, H, C):
     """conv -> BN with the statistics taken from the convolution kernel's per-tile records."""
