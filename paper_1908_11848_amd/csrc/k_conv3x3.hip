@@ -30,6 +30,71 @@ namespace {
 
 constexpr int THREADS = 256;
 
+// ---- gradient w.r.t. the filter by minimal filtering F(3x3, 2x2):
+//      dw[tap][ci][co] = sum over pixels x[pixel + tap][ci] dy[pixel][co]; per 2x2 tile of dy and its 4x4 patch of x,
+//      dw += A^T [ (B^T x B) .* (G dy G^T) ] A with B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 -1 0 1],
+//      G = [1 0; .5 .5; .5 -.5; 0 1], A^T = [1 1 1 0; 0 1 -1 0; 0 1 1 1].  The sum over tiles is taken in the
+//      transformed domain by the matrix cores, M_xi[ci][co] += sum over tiles XT_xi[ci][tile] DT_xi[tile][co]
+//      (16 products instead of 36 per tile), and A^T M A is applied once at the end.
+// One run of 16 tiles: the lane (l16, q) transforms, as scalars, the patch (its input channel) and the dy tile (its
+// output channel) of tile 4q + s for each of the four MFMA steps s.  at(tile) locates a tile once; x_at(o, r, c) and
+// d_at(o, i, j) fetch the patch and dy elements from there.
+template <class At, class XAt, class DAt>
+__device__ __forceinline__ void dfilter_run(floatx4 (&M)[16], int q, At at, XAt x_at, DAt d_at) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const auto tile = at(4 * q + s);
+        float XT[16], DT[16];
+        {
+            float t[4][4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                float x[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) x[r] = x_at(tile, r, c);
+                t[0][c] = x[0] - x[2]; t[1][c] = x[1] + x[2]; t[2][c] = x[2] - x[1]; t[3][c] = x[3] - x[1];
+            }
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                XT[4 * a] = t[a][0] - t[a][2]; XT[4 * a + 1] = t[a][1] + t[a][2];
+                XT[4 * a + 2] = t[a][2] - t[a][1]; XT[4 * a + 3] = t[a][3] - t[a][1];
+            }
+        }
+        {
+            float u[4][2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float d0 = d_at(tile, 0, j), d1 = d_at(tile, 1, j);
+                u[0][j] = d0; u[1][j] = 0.5f * (d0 + d1); u[2][j] = 0.5f * (d0 - d1); u[3][j] = d1;
+            }
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                DT[4 * a] = u[a][0]; DT[4 * a + 1] = 0.5f * (u[a][0] + u[a][1]);
+                DT[4 * a + 2] = 0.5f * (u[a][0] - u[a][1]); DT[4 * a + 3] = u[a][1];
+            }
+        }
+#pragma unroll
+        for (int xi = 0; xi < 16; ++xi) M[xi] = __builtin_amdgcn_mfma_f32_16x16x4f32(XT[xi], DT[xi], M[xi], 0, 0, 0);
+    }
+}
+
+// dw = A^T M A; call after mma::drain().
+__device__ __forceinline__ void dfilter_finish(const floatx4 (&M)[16], floatx4 (&dw)[9]) {
+    floatx4 S[3][4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        S[0][b] = M[b] + M[4 + b] + M[8 + b];
+        S[1][b] = M[4 + b] - M[8 + b];
+        S[2][b] = M[4 + b] + M[8 + b] + M[12 + b];
+    }
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        dw[3 * r] = S[r][0] + S[r][1] + S[r][2];
+        dw[3 * r + 1] = S[r][1] - S[r][2];
+        dw[3 * r + 2] = S[r][1] + S[r][2] + S[r][3];
+    }
+}
+
 template <int C, int HW, int R, int NSPLIT>
 struct Cfg {
     static constexpr int CN = C / NSPLIT;          // output channels per workgroup
@@ -373,14 +438,8 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_wav
             }
         }
     if constexpr (WG) {
-        // ---- d-filter of the same layer from the two LDS tiles, while the epilogue's operands are in flight:
-        //      dw[tap][ci][co] = sum over pixels x[pixel + tap][ci] dx[pixel][co], again by minimal filtering, now
-        //      F(3x3, 2x2): per 2x2 tile of dx and its 4x4 patch of x, dw += A^T [ (B^T x B) .* (G dx G^T) ] A with
-        //      B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 -1 0 1], G = [1 0; .5 .5; .5 -.5; 0 1], A^T = [1 1 1 0; 0 1 -1 0; 0 1 1 1].
-        //      The sum over tiles is taken in the transformed domain by the matrix cores, M_xi[ci][co] += sum over
-        //      tiles XT_xi[ci][tile] DT_xi[tile][co] (16 products instead of 36 per tile), and A^T M A is applied once
-        //      at the end.  A lane transforms, as scalars, the patches (channel 16 cit + l16) and dx tiles (channel
-        //      16 cot + l16) of the four tiles it feeds to the four MFMAs of a run.
+        // ---- d-filter of the same layer from the two LDS tiles, while the epilogue's operands are in flight (see
+        //      dfilter_run): x patches from Xs2, dx tiles from the interior of Xs.
         //      C = 16: one 16x16 tile of (ci, co), the four wavefronts take one run each and are summed in a fixed
         //      order; C = 32: wavefront w owns tile (w / 2, w % 2) and walks both runs.
         constexpr bool SPLIT_K = (C == 16);
@@ -390,63 +449,17 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_wav
 #pragma unroll
         for (int xi = 0; xi < 16; ++xi) M[xi] = floatx4{0.f, 0.f, 0.f, 0.f};
         for (int run = SPLIT_K ? wave : 0; run < K::WRUNS; run += SPLIT_K ? 4 : 1) {
-#pragma unroll
-            for (int s_ = 0; s_ < 4; ++s_) {
-                const int g = run * 16 + 4 * q + s_;
-                const int o = (2 * (g / TXN) * K::TW + 2 * (g % TXN)) * K::LDC;      // the patch's corner in both halo tiles
-                float XT[16], DT[16];
-                {
-                    float t[4][4];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        float x[4];
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) x[r] = Xs2[o + (r * K::TW + c) * K::LDC + 16 * cit + l16];
-                        t[0][c] = x[0] - x[2]; t[1][c] = x[1] + x[2]; t[2][c] = x[2] - x[1]; t[3][c] = x[3] - x[1];
-                    }
-#pragma unroll
-                    for (int a_ = 0; a_ < 4; ++a_) {
-                        XT[4 * a_] = t[a_][0] - t[a_][2]; XT[4 * a_ + 1] = t[a_][1] + t[a_][2];
-                        XT[4 * a_ + 2] = t[a_][2] - t[a_][1]; XT[4 * a_ + 3] = t[a_][3] - t[a_][1];
-                    }
-                }
-                {
-                    float d[2][2], u[4][2];
-#pragma unroll
-                    for (int i = 0; i < 2; ++i)
-#pragma unroll
-                        for (int j = 0; j < 2; ++j) d[i][j] = Xs[o + ((i + 1) * K::TW + j + 1) * K::LDC + 16 * cot + l16];
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        u[0][j] = d[0][j]; u[1][j] = 0.5f * (d[0][j] + d[1][j]); u[2][j] = 0.5f * (d[0][j] - d[1][j]); u[3][j] = d[1][j];
-                    }
-#pragma unroll
-                    for (int a_ = 0; a_ < 4; ++a_) {
-                        DT[4 * a_] = u[a_][0]; DT[4 * a_ + 1] = 0.5f * (u[a_][0] + u[a_][1]);
-                        DT[4 * a_ + 2] = 0.5f * (u[a_][0] - u[a_][1]); DT[4 * a_ + 3] = u[a_][1];
-                    }
-                }
-#pragma unroll
-                for (int xi = 0; xi < 16; ++xi) M[xi] = __builtin_amdgcn_mfma_f32_16x16x4f32(XT[xi], DT[xi], M[xi], 0, 0, 0);
-            }
+            dfilter_run(M, q,
+                        [&](int tile) {                 // the patch's corner in both halo tiles
+                            const int g = run * 16 + tile;
+                            return (2 * (g / TXN) * K::TW + 2 * (g % TXN)) * K::LDC;
+                        },
+                        [&](int o, int r, int c) { return Xs2[o + (r * K::TW + c) * K::LDC + 16 * cit + l16]; },
+                        [&](int o, int i, int j) { return Xs[o + ((i + 1) * K::TW + j + 1) * K::LDC + 16 * cot + l16]; });
         }
         mma::drain();
         floatx4 dwa[9];
-        {
-            floatx4 S[3][4];
-#pragma unroll
-            for (int b_ = 0; b_ < 4; ++b_) {
-                S[0][b_] = M[b_] + M[4 + b_] + M[8 + b_];
-                S[1][b_] = M[4 + b_] - M[8 + b_];
-                S[2][b_] = M[4 + b_] + M[8 + b_] + M[12 + b_];
-            }
-#pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                dwa[3 * r] = S[r][0] + S[r][1] + S[r][2];
-                dwa[3 * r + 1] = S[r][1] - S[r][2];
-                dwa[3 * r + 2] = S[r][1] + S[r][2] + S[r][3];
-            }
-        }
+        dfilter_finish(M, dwa);
         float* pout = wg.partial + (long)blockIdx.x * 9 * C * C;
         if constexpr (SPLIT_K) {
             static_assert(!SPLIT_K || 4 * 9 * C * C <= 2 * K::XS + K::SS + K::PS, "room for the four partial sums");
@@ -702,11 +715,10 @@ int conv3x3_direct_stat_parts(int N, int HW, int C) {
 // Gradient w.r.t. the filter of the same convolutions, stage 1 of 2: one workgroup per band of
 // R rows of one image; the x halo tile and the dy tile sit in LDS and all nine taps
 //   dw[tap][ci][co] += sum_{pixels of the band} x[pixel + tap][ci] * dy[pixel][co]
-// are accumulated from them (x and dy are read from memory once).  The matrix-core tile is
-// 16 (ci) x 16 (co), the reduction runs over pixels in chunks of 16.
-//   C = 16: one tile per tap; the four wavefronts split the pixel chunks and are summed in a
-//           fixed order at the end.
-//   C = 32: four tiles per tap; wavefront w owns tile (w / 2, w % 2) and walks all pixels.
+// are accumulated from them (x and dy are read from memory once), by minimal filtering (dfilter_run).  The
+// matrix-core tile is 16 (ci) x 16 (co), the reduction runs over tiles of 2x2 pixels in runs of 16.
+//   C = 16: one (ci, co) tile; the four wavefronts take one run each and are summed in a fixed order at the end.
+//   C = 32: four (ci, co) tiles; wavefront w owns tile (w / 2, w % 2) and walks both runs.
 // Output: partial[workgroup][tap][ci][co]; stage 2 (wgrad_reduce_kernel) sums over workgroups.
 namespace {
 
@@ -716,8 +728,8 @@ struct WCfg {
     static constexpr int TW = HW + 2;
     static constexpr int XS = (R + 2) * TW * LDC;
     static constexpr int DS = R * HW * LDC;
-    static constexpr int CHUNKS = R * HW / 16;
     static constexpr bool SPLIT_K = (C == 16);
+    static_assert(!SPLIT_K || (R / 2) * (HW / 2) == 64, "one run of 16 tiles per wavefront");
     static constexpr int RED = SPLIT_K ? 4 * 9 * C * C : 0;
     static constexpr size_t LDS_BYTES = (size_t)((XS + DS) > RED ? (XS + DS) : RED) * sizeof(float);
 };
@@ -756,27 +768,19 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_kernel(const float* __restri
 
     const int l16 = lane & 15, q = lane >> 4;
     const int cit = K::SPLIT_K ? 0 : wave >> 1, cot = K::SPLIT_K ? 0 : wave & 1;
-    floatx4 acc[9];
+    constexpr int TXN = HW / 2, WRUNS = (R / 2) * TXN / 16;
+    floatx4 M[16];
 #pragma unroll
-    for (int t = 0; t < 9; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-    for (int c = K::SPLIT_K ? wave : 0; c < K::CHUNKS; c += K::SPLIT_K ? 4 : 1) {
-        float b[4];
-        int xo[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int p = 16 * c + 4 * q + s;
-            b[s] = Ds[p * K::LDC + 16 * cot + l16];
-            xo[s] = ((p / HW) * K::TW + (p % HW)) * K::LDC + 16 * cit + l16;
-        }
-#pragma unroll
-        for (int t = 0; t < 9; ++t) {
-            const int toff = ((t / 3) * K::TW + (t % 3)) * K::LDC;
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Xs[xo[s] + toff], b[s], acc[t], 0, 0, 0);
-        }
+    for (int xi = 0; xi < 16; ++xi) M[xi] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int run = K::SPLIT_K ? wave : 0; run < WRUNS; run += K::SPLIT_K ? 4 : 1) {
+        dfilter_run(M, q,
+                    [&](int tile) { return make_int2(2 * ((run * 16 + tile) / TXN), 2 * ((run * 16 + tile) % TXN)); },
+                    [&](int2 o, int r, int c) { return Xs[((o.x + r) * K::TW + o.y + c) * K::LDC + 16 * cit + l16]; },
+                    [&](int2 o, int i, int j) { return Ds[((o.x + i) * HW + o.y + j) * K::LDC + 16 * cot + l16]; });
     }
     mma::drain();
+    floatx4 acc[9];
+    dfilter_finish(M, acc);
     float* out = partial + (long)blockIdx.x * 9 * C * C;
     if constexpr (K::SPLIT_K) {
         __syncthreads();                              // tiles no longer needed: reuse LDS for the 4 partial sums
@@ -798,7 +802,7 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_kernel(const float* __restri
 
 // The same for the last stage (64 channels, 8x8 images), where one image is only four pixel chunks and the
 // result is as large as 9 x 64 x 64: a workgroup owns 16 of the input channels (wavefront w: output channels
-// 16w..16w+15, all nine taps, 9 accumulator tiles) and IMGS whole images, one after the other; the next image's
+// 16w..16w+15, the 16 accumulator tiles of the transformed domain) and IMGS whole images, one after the other; the next image's
 // x halo tile (its 16 channels only) and dy tile are fetched into registers while the matrix cores work on the
 // current one (two LDS buffers, one barrier per image).  Output: partial[image group][tap][ci][co], the
 // workgroup's 16 ci rows of it.
@@ -850,9 +854,9 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_wide_kernel(const float* __r
             *reinterpret_cast<float4*>(&Ds[(idx / (C / 4)) * LDB + 4 * (idx % (C / 4))]) = rd[e];
         }
     };
-    floatx4 acc[9];
+    floatx4 M[16];
 #pragma unroll
-    for (int t = 0; t < 9; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int xi = 0; xi < 16; ++xi) M[xi] = floatx4{0.f, 0.f, 0.f, 0.f};
     fetch(n0);
     for (int i = 0; i < nimg; ++i) {
         stage(i & 1);
@@ -860,26 +864,15 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_wide_kernel(const float* __r
         if (i + 1 < nimg) fetch(n0 + i + 1);
         const float* Xs = lds + (i & 1) * BUF;
         const float* Ds = Xs + XS;
-#pragma unroll
-        for (int c = 0; c < HW * HW / 16; ++c) {
-            float b[4];
-            int xo[4];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int p = 16 * c + 4 * q + s;
-                b[s] = Ds[p * LDB + 16 * cot + l16];
-                xo[s] = ((p / HW) * TW + (p % HW)) * LDA + l16;
-            }
-#pragma unroll
-            for (int t = 0; t < 9; ++t) {
-                const int toff = ((t / 3) * TW + (t % 3)) * LDA;
-#pragma unroll
-                for (int s = 0; s < 4; ++s)
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Xs[xo[s] + toff], b[s], acc[t], 0, 0, 0);
-            }
-        }
+        // the image is one run: 4 x 4 tiles of 2x2 pixels
+        dfilter_run(M, q,
+                    [&](int tile) { return make_int2(2 * (tile / 4), 2 * (tile % 4)); },
+                    [&](int2 o, int r, int c) { return Xs[((o.x + r) * TW + o.y + c) * LDA + l16]; },
+                    [&](int2 o, int i_, int j) { return Ds[((o.x + i_) * HW + o.y + j) * LDB + 16 * cot + l16]; });
     }
     mma::drain();
+    floatx4 acc[9];
+    dfilter_finish(M, acc);
     float* out = partial + (long)grp * 9 * C * C;
 #pragma unroll
     for (int t = 0; t < 9; ++t)
