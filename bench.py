@@ -67,8 +67,9 @@ def main():
         segs = B.dssp_model_segments(B.model_id(wl["model"]), wl["n_classes"])
         w0 = inputs.init_weights(segs, wl["config"])
         xs, ys = inputs.batches(wl["config"], K, wl["pool"], wl["batch"], wl["n_classes"])
+        rates = [1.0 / float(np.mean(row)) for row in d]         # a worker that iterates twice as fast pushes twice as often
         em = Emulation(wl["model"], K, wl["s_L"], wl["r_max"], wl["lr"], w0, wl["batch"], wl["n_classes"], xs, ys,
-                       worker_streams=a.worker_streams)
+                       worker_streams=a.worker_streams, rates=rates)
         n = int(w0.size)
     sched = em.schedule(d, log=False, fused_pull=True)       # the pull of a worker granted OK by its own push rides in the apply kernel
     sched.advance(a.warmup)

@@ -824,44 +824,43 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_wide_kernel(const float* __r
     const int n0 = grp * IMGS;
     const int nimg = min(IMGS, N - n0);
     float4 rx[XV], rd[DV];
-    auto fetch = [&](int n) {
 #pragma unroll
-        for (int e = 0; e < XV; ++e) {
-            const int idx = tid + e * THREADS;
-            const int v = idx % (CIW / 4), pix = idx / (CIW / 4);
-            const int h = pix / TW - 1, w = pix % TW - 1;
-            rx[e] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (pix < TW * TW && h >= 0 && h < HW && w >= 0 && w < HW)
-                rx[e] = *reinterpret_cast<const float4*>(x + (((long)n * HW + h) * HW + w) * C + CIW * cit + 4 * v);
-        }
+    for (int e = 0; e < XV; ++e) rx[e] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int e = 0; e < DV; ++e) {
-            const int idx = tid + e * THREADS;
-            rd[e] = *reinterpret_cast<const float4*>(dy + (long)n * HW * HW * C + 4 * (long)idx);
-        }
-    };
-    auto stage = [&](int buf) {
-        float* Xs = lds + buf * BUF;
-        float* Ds = Xs + XS;
-#pragma unroll
-        for (int e = 0; e < XV; ++e) {
-            const int idx = tid + e * THREADS;
-            if (idx < TW * TW * (CIW / 4)) *reinterpret_cast<float4*>(&Xs[(idx / (CIW / 4)) * LDA + 4 * (idx % (CIW / 4))]) = rx[e];
-        }
-#pragma unroll
-        for (int e = 0; e < DV; ++e) {
-            const int idx = tid + e * THREADS;
-            *reinterpret_cast<float4*>(&Ds[(idx / (C / 4)) * LDB + 4 * (idx % (C / 4))]) = rd[e];
-        }
-    };
+    for (int e = 0; e < DV; ++e) rd[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+    // written out as macros: with lambdas that capture the two arrays the compiler kept rd in scratch memory
+#define WIDE_FETCH(n)                                                                                                      \
+    _Pragma("unroll") for (int e = 0; e < XV; ++e) {                                                                       \
+        const int idx = tid + e * THREADS;                                                                                 \
+        const int v = idx % (CIW / 4), pix = idx / (CIW / 4);                                                              \
+        const int h = pix / TW - 1, w = pix % TW - 1;                                                                      \
+        rx[e] = make_float4(0.f, 0.f, 0.f, 0.f);                                                                           \
+        if (pix < TW * TW && h >= 0 && h < HW && w >= 0 && w < HW)                                                         \
+            rx[e] = *reinterpret_cast<const float4*>(x + (((long)(n) * HW + h) * HW + w) * C + CIW * cit + 4 * v);         \
+    }                                                                                                                      \
+    _Pragma("unroll") for (int e = 0; e < DV; ++e)                                                                         \
+        rd[e] = *reinterpret_cast<const float4*>(dy + (long)(n) * HW * HW * C + 4 * (long)(tid + e * THREADS));
+#define WIDE_STAGE(buf)                                                                                                    \
+    {                                                                                                                      \
+        float* Xw = lds + (buf) * BUF;                                                                                     \
+        float* Dw = Xw + XS;                                                                                               \
+        _Pragma("unroll") for (int e = 0; e < XV; ++e) {                                                                   \
+            const int idx = tid + e * THREADS;                                                                             \
+            if (idx < TW * TW * (CIW / 4)) *reinterpret_cast<float4*>(&Xw[(idx / (CIW / 4)) * LDA + 4 * (idx % (CIW / 4))]) = rx[e]; \
+        }                                                                                                                  \
+        _Pragma("unroll") for (int e = 0; e < DV; ++e) {                                                                   \
+            const int idx = tid + e * THREADS;                                                                             \
+            *reinterpret_cast<float4*>(&Dw[(idx / (C / 4)) * LDB + 4 * (idx % (C / 4))]) = rd[e];                          \
+        }                                                                                                                  \
+    }
     floatx4 M[16];
 #pragma unroll
     for (int xi = 0; xi < 16; ++xi) M[xi] = floatx4{0.f, 0.f, 0.f, 0.f};
-    fetch(n0);
+    WIDE_FETCH(n0)
     for (int i = 0; i < nimg; ++i) {
-        stage(i & 1);
+        WIDE_STAGE(i & 1)
         __syncthreads();
-        if (i + 1 < nimg) fetch(n0 + i + 1);
+        if (i + 1 < nimg) { WIDE_FETCH(n0 + i + 1) }
         const float* Xs = lds + (i & 1) * BUF;
         const float* Ds = Xs + XS;
         // the image is one run: 4 x 4 tiles of 2x2 pixels
@@ -870,6 +869,8 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_wide_kernel(const float* __r
                     [&](int2 o, int r, int c) { return Xs[((o.x + r) * TW + o.y + c) * LDA + l16]; },
                     [&](int2 o, int i_, int j) { return Ds[((o.x + i_) * HW + o.y + j) * LDB + 16 * cot + l16]; });
     }
+#undef WIDE_FETCH
+#undef WIDE_STAGE
     mma::drain();
     floatx4 acc[9];
     dfilter_finish(M, acc);

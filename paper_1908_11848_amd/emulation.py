@@ -11,9 +11,20 @@ from . import binding as B
 from . import driver
 
 
+def deal(rates, n_lanes):
+    """Lane of each worker such that the lanes' sums of rates are about equal (longest processing time first)."""
+    load = [0.0] * n_lanes
+    lane_of = [0] * len(rates)
+    for p in sorted(range(len(rates)), key=lambda p: (-rates[p], p)):
+        lane = min(range(n_lanes), key=lambda l: (load[l], l))
+        lane_of[p] = lane
+        load[lane] += rates[p]
+    return lane_of
+
+
 class Emulation:
     def __init__(self, model, K, s_L, r_max, lr, w0, batch=0, n_classes=0, xs=None, ys=None, grads=None,
-                 device="cuda:0", worker_streams=None, server_stream=False):
+                 device="cuda:0", worker_streams=None, server_stream=False, rates=None):
         """model: 'mlp' | 'alexnet_ds' | 'resnet<d>' | 'none'.
         w0: float32 initial weights.  xs[p][j] / ys[p][j]: pool of mini-batches of worker p
         (cycled); grads[p]: fixed gradient buffers for model 'none' (server stress).
@@ -23,6 +34,9 @@ class Emulation:
         uneven spread of the workers over the queues costs throughput.  A given number of streams is
         spread over the queues as evenly as they allow.  Ordering between workers goes through the
         library's events either way, so results do not depend on it.
+        rates: expected pushes per unit time of each worker (any scale).  Given them, the workers are dealt onto
+        the streams so that every stream gets about the same share of the work (greedily, fastest worker first,
+        each to the stream with the smallest sum so far) instead of round-robin.
         server_stream: give the server's applies a stream of their own instead of the pusher's (same results;
         slower when that stream shares a hardware queue with a worker's)."""
         if not torch.cuda.is_available():
@@ -44,7 +58,8 @@ class Emulation:
                 self.grad[p].copy_(torch.from_numpy(np.ascontiguousarray(grads[p], dtype=np.float32)))
         self.loss = torch.zeros(K, dtype=torch.float32, device=self.dev)
         lanes, self.hardware_queues = self._lanes(K, worker_streams)
-        self.streams = [lanes[p % len(lanes)] for p in range(K)]
+        self.lane_of = deal(rates, len(lanes)) if rates is not None else [p % len(lanes) for p in range(K)]
+        self.streams = [lanes[self.lane_of[p]] for p in range(K)]
         self.ctx = B.dssp_create(self.w, n, K, s_L, r_max, lr)
         if server_stream:
             self.streams.append(torch.cuda.Stream(device=self.dev))

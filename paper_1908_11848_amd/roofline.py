@@ -12,21 +12,23 @@ what the hardware-counter passes are taken on:
         -- python3 -m paper_1908_11848_amd.roofline
 
 Algorithmic work per launch, with T = 4 * N * H * H * C bytes (one activation tensor of the stage) and
-F = 2 * N * H * H * C * 9 * C FLOP (one 3x3 convolution):
-    conv_fwd       plain forward convolution + statistics records            F,  2 T  (read x, write y)
-    conv_fwd_bn    records merge + forward convolution with BN + shortcut    F,  4 T  (read z, shortcut; write a, y)
+W = (4/9) * 2 * N * H * H * C * 9 * C FLOP, the matrix-core work of one 3x3 convolution by minimal filtering
+(16 instead of 36 multiplications per 2x2 tile and channel pair; the direct form would be 9/4 W):
+    conv_fwd       plain forward convolution + statistics records            W,  2 T  (read x, write y)
+    conv_fwd_bn    records merge + forward convolution with BN + shortcut    W,  4 T  (read z, shortcut; write a, y)
                    + ReLU folded into its loader (2 kernels)
-    conv_bwd_fused d-input AND d-filter convolution of a layer in one kernel 2F, 6 T  (read dz, xc, add, x, xc of the next BN;
+    conv_bwd_fused d-input AND d-filter convolution of a layer in one kernel 2W, 6 T  (read dz, xc, add, x, xc of the next BN;
                    (stages 1-2): BN backward in its loader, shortcut                  write out) + its own partial sums and
                    gradient, ReLU mask + sum records in its epilogue,                 the carried reduction's
                    carrying the previous layer's d-filter reduction
-    conv_dgrad_bn  the same without the d-filter part (stage 3), dx stored   F,  7 T  + the carried reduction's partial sums
-    conv_wgrad     d-filter convolution, stage 1 (stage 3), carrying the     F,  2 T + its partial sums
+    conv_dgrad_bn  the same without the d-filter part (stage 3), dx stored   W,  7 T  + the carried reduction's partial sums
+    conv_wgrad     d-filter convolution, stage 1 (stage 3), carrying the     W,  2 T + its partial sums
                    BN sums job
     bn_fwd / bn_bwd  stand-alone batch-norm kernels (irregular layers only)      4 T / 7 T
     apply / pull   server update and snapshot copy                               12 / 8 bytes per parameter
-A case is bound by whichever of its two floors is higher: F at 157.3 TFLOP/s (fp32 matrix cores: 256 CUs
-x 4 SIMDs x 64 FLOP/cycle x 2.4 GHz) or its bytes at 8 TB/s (HBM).  HBM traffic per launch (`traffic`)
+A case is bound by whichever of its two floors is higher: its FLOP at 157.3 TFLOP/s (fp32 matrix cores: 256 CUs
+x 4 SIMDs x 64 FLOP/cycle x 2.4 GHz) or its bytes at 8 TB/s (HBM); with minimal filtering that is HBM for every
+3x3 case.  HBM traffic per launch (`traffic`)
 comes from profiles/traffic_counters.json (counter values scaled by what the same counter reads
 for the snapshot-copy kernel of known size) and is reported as null as soon as the kernel's
 source file differs from the one the counters were taken on.
@@ -122,7 +124,7 @@ def _conv_cases(H, C, dev):
     E = 9 * C * C
     ch = ctypes.c_int(0)
     T = 4.0 * M * C
-    F = 2.0 * M * C * 9 * C
+    F = 2.0 * M * C * 9 * C * 4.0 / 9.0          # executed on the matrix cores (minimal filtering)
     fwd = lambda s: L.dsspk_conv_fwd(s, x.data_ptr(), w.data_ptr(), None, z.data_ptr(), N, H, H, C, C, 3, 3, 1, 1, 0, recA.data_ptr())
     fwd_bn = lambda s: L.dsspk_conv_fwd_prebn(s, z.data_ptr(), recA.data_ptr(), parts, gamma.data_ptr(), beta.data_ptr(), 1e-5,
                                               sc.data_ptr(), a.data_ptr(), stats_o.data_ptr(), w.data_ptr(), y.data_ptr(),

@@ -146,3 +146,15 @@ def test_paradigm_sweep_in_virtual_time():
         assert res["BSP"]["staleness_max"] == 0 and res["SSP s=3"]["staleness_max"] <= 3
         assert res["SSP s=15"]["staleness_max"] <= 15 and res["DSSP (3,12)"]["staleness_max"] <= 15
         assert all(v["pushes"] == 100 * K for v in res.values())
+
+
+def test_workers_are_dealt_onto_streams_by_their_rates():
+    from paper_1908_11848_amd.emulation import deal
+    rates = [1.0, 0.4, 0.9, 0.5, 0.8, 0.6, 0.7, 0.45]
+    lane_of = deal(rates, 4)
+    assert sorted(set(lane_of)) == [0, 1, 2, 3]
+    load = [sum(r for r, l in zip(rates, lane_of) if l == lane) for lane in range(4)]
+    assert max(load) - min(load) <= 0.11 and lane_of[0] == lane_of[1]          # fastest shares with slowest
+    assert deal(rates, 4) == lane_of                                          # deterministic
+    assert deal([1.0] * 8, 4) == [0, 1, 2, 3, 0, 1, 2, 3]                     # equal workers: round-robin
+    assert deal([3.0, 1.0], 4) == [0, 1] and deal([1.0, 2.0, 3.0], 1) == [0, 0, 0]
