@@ -30,6 +30,17 @@ namespace {
 
 constexpr int THREADS = 256;
 
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8) and every XCD has an L2 of its
+// own.  Tiles that are neighbours in memory share data - halo rows between the bands of an image, the whole input
+// tile between the channel splits of a band, dy between the input-channel slices of the last stage's d-filter
+// kernel - so consecutive tiles go to ONE XCD: workgroup b takes tile (b mod 8) * (n / 8) + b / 8, and what the
+// first of them fetched is in that L2 for the next (without this, halo rows and shared tiles come over the fabric
+// once per XCD that touches them: 1.1x to 1.7x the operands' bytes).  Needs n to be a multiple of 8.
+__device__ __forceinline__ int xcd_tile(int block, int n_blocks) {
+    constexpr int XCDS = 8;
+    return n_blocks % XCDS ? block : (block % XCDS) * (n_blocks / XCDS) + block / XCDS;
+}
+
 // ---- gradient w.r.t. the filter by minimal filtering F(3x3, 2x2):
 //      dw[tap][ci][co] = sum over pixels x[pixel + tap][ci] dy[pixel][co]; per 2x2 tile of dy and its 4x4 patch of x,
 //      dw += A^T [ (B^T x B) .* (G dy G^T) ] A with B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 -1 0 1],
@@ -200,9 +211,10 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_wav
     const int l16 = lane & 15, q = lane >> 4;
     const int wave_n = wave % K::WAVES_N, wave_m = wave / K::WAVES_N;
     constexpr int BANDS = HW / R;
-    const int split = blockIdx.x % NSPLIT;
-    const int band = (blockIdx.x / NSPLIT) % BANDS;
-    const int n = blockIdx.x / (NSPLIT * BANDS);
+    const int tile = xcd_tile(blockIdx.x, conv_blocks);
+    const int split = tile % NSPLIT;
+    const int band = (tile / NSPLIT) % BANDS;
+    const int n = tile / (NSPLIT * BANDS);
     const int r_base = band * R;                    // first output row of the band
     const int co_base = split * K::CN;
     const int co = co_base + 16 * wave_n + l16;     // this lane's output channel (column of the MFMA tile)
@@ -460,7 +472,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(min_wav
         mma::drain();
         floatx4 dwa[9];
         dfilter_finish(M, dwa);
-        float* pout = wg.partial + (long)blockIdx.x * 9 * C * C;
+        float* pout = wg.partial + (long)tile * 9 * C * C;
         if constexpr (SPLIT_K) {
             static_assert(!SPLIT_K || 4 * 9 * C * C <= 2 * K::XS + K::SS + K::PS, "room for the four partial sums");
             __syncthreads();                              // both tiles are no longer needed: reuse LDS for the 4 partial sums
@@ -747,7 +759,8 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_kernel(const float* __restri
     float* Ds = lds + K::XS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int BANDS = HW / R;
-    const int band = blockIdx.x % BANDS, n = blockIdx.x / BANDS;
+    const int tile = xcd_tile(blockIdx.x, own_blocks);
+    const int band = tile % BANDS, n = tile / BANDS;
     const int r_base = band * R;
     constexpr int V = C / 4;
     for (int idx = tid; idx < (R + 2) * K::TW * V; idx += THREADS) {
@@ -781,7 +794,7 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_kernel(const float* __restri
     mma::drain();
     floatx4 acc[9];
     dfilter_finish(M, acc);
-    float* out = partial + (long)blockIdx.x * 9 * C * C;
+    float* out = partial + (long)tile * 9 * C * C;
     if constexpr (K::SPLIT_K) {
         __syncthreads();                              // tiles no longer needed: reuse LDS for the 4 partial sums
         float* Red = lds;
@@ -820,7 +833,8 @@ __global__ __launch_bounds__(THREADS) void wgrad3x3_wide_kernel(const float* __r
     }
     const int tid = threadIdx.x, lane = tid & 63, cot = tid >> 6;
     const int l16 = lane & 15, q = lane >> 4;
-    const int cit = blockIdx.x % (C / CIW), grp = blockIdx.x / (C / CIW);
+    const int tile = xcd_tile(blockIdx.x, own_blocks);
+    const int cit = tile % (C / CIW), grp = tile / (C / CIW);
     const int n0 = grp * IMGS;
     const int nimg = min(IMGS, N - n0);
     float4 rx[XV], rd[DV];

@@ -197,11 +197,12 @@ def cases(dev, n_params=N_PARAMS):
         g = torch.randn(n, device=dev) * 1e-3
         dst = torch.empty(n, device=dev)
         st = torch.zeros(2, dtype=torch.int64, device=dev)
-        out.append(("apply_%d" % n, "apply_kernel (%d params)" % n, 0.0, 12.0 * n,
-                    lambda s, w=w, g=g, st=st, n=n: L.dsspk_apply(s, w.data_ptr(), g.data_ptr(), n, 1e-3, st.data_ptr(), 1),
+        pw, pg, pd, ps = w.data_ptr(), g.data_ptr(), dst.data_ptr(), st.data_ptr()      # pointers taken once: these
+        out.append(("apply_%d" % n, "apply_kernel (%d params)" % n, 0.0, 12.0 * n,      # kernels are as short as a launch
+                    lambda s, pw=pw, pg=pg, ps=ps, n=n: L.dsspk_apply(s, pw, pg, n, 1e-3, ps, 1),
                     None, ("k_server.hip",), (w, g, st)))
         out.append(("pull_%d" % n, "pull_kernel (%d params)" % n, 0.0, 8.0 * n,
-                    lambda s, w=w, dst=dst, st=st, n=n: L.dsspk_pull(s, dst.data_ptr(), w.data_ptr(), n, st[1:].data_ptr(), st.data_ptr()),
+                    lambda s, pw=pw, pd=pd, ps=ps, n=n: L.dsspk_pull(s, pd, pw, n, ps + 8, ps),
                     None, ("k_server.hip",), (w, dst, st)))
     assert [c[0] for c in out] == [k for k, _, _ in case_list(n_params)]
     return out
