@@ -32,6 +32,15 @@ int dsspk_apply_pull(void* stream, float* w_dev, const float* g_dev, float* dst_
  * leading dimension ldc.  bias_dev may be NULL. */
 int dsspk_gemm(void* stream, const float* A_dev, long a_rs, long a_cs, const float* B_dev, long b_rs, long b_cs,
                float* C_dev, long ldc, int M, int N, int K, const float* bias_dev, int relu);
+/* The same product with the reduction index K split over `layers` layers of workgroups, for products with few
+ * output tiles and a long K (the forward pass of a wide fully connected layer at a small batch would otherwise
+ * occupy a dozen compute units): every layer writes its partial product to scratch_dev ([layers][M][N] floats), a
+ * second kernel adds the layers in order and applies bias / ReLU.  dsspk_gemm_splitk_layers proposes the number of
+ * layers (1: the plain kernel is used and scratch_dev may be NULL). */
+int dsspk_gemm_splitk_layers(int M, int N, int K);
+int dsspk_gemm_splitk(void* stream, const float* A_dev, long a_rs, long a_cs, const float* B_dev, long b_rs, long b_cs,
+                      float* C_dev, long ldc, int M, int N, int K, const float* bias_dev, int relu,
+                      float* scratch_dev, int layers);
 /* out[j] = sum_i X[i][j], X is [M][N] row-major.  Fixed summation order (row slabs, then the slabs). */
 int dsspk_colsum(void* stream, const float* X_dev, float* out_dev, float* scratch_dev, long M, int N);
 /* Floats of scratch_dev dsspk_colsum needs for an [M][N] matrix (0 for short matrices: scratch_dev may be NULL). */

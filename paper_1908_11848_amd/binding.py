@@ -63,6 +63,9 @@ _SIGNATURES = {
     "dsspk_apply_pull": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, ctypes.c_float, c_void_p, c_void_p, ctypes.c_uint64]),
     "dsspk_gemm": (c_int, [c_void_p, c_void_p, c_long, c_long, c_void_p, c_long, c_long, c_void_p, c_long,
                            c_int, c_int, c_int, c_void_p, c_int]),
+    "dsspk_gemm_splitk_layers": (c_int, [c_int, c_int, c_int]),
+    "dsspk_gemm_splitk": (c_int, [c_void_p, c_void_p, c_long, c_long, c_void_p, c_long, c_long, c_void_p, c_long,
+                                  c_int, c_int, c_int, c_void_p, c_int, c_void_p, c_int]),
     "dsspk_colsum": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_long, c_int]),
     "dsspk_colsum_scratch_floats": (c_size_t, [c_long, c_int]),
     "dsspk_conv_fwd": (c_int, [c_void_p] * 5 + [c_int] * 10 + [c_void_p]),

@@ -16,11 +16,16 @@ template <bool A_FAST_K, bool B_FAST_N>
 __global__ __launch_bounds__(THREADS) void gemm_kernel(const float* __restrict__ A, long a_rs, long a_cs,
                                                        const float* __restrict__ B, long b_rs, long b_cs,
                                                        float* __restrict__ C, long ldc, int M, int N, int K,
-                                                       const float* __restrict__ bias, int relu) {
+                                                       const float* __restrict__ bias, int relu, int k_per_layer) {
     __shared__ __attribute__((aligned(16))) float As[2][BM * mma::LDK];
     __shared__ __attribute__((aligned(16))) float Bs[2][BN * mma::LDK];      // stored [col][k]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    // split-K: layer z of the grid takes the reduction indices [z * k_per_layer, (z + 1) * k_per_layer) and writes its
+    // partial product to the z-th [M][N] slab of C (the caller passes scratch, no bias, no ReLU)
+    const int k_lo = blockIdx.z * k_per_layer;
+    K = min(K, k_lo + k_per_layer);
+    C += (long)blockIdx.z * M * N;
     floatx4 acc[2][2];
     mma::zero(acc);
     float ra[4], rb[4];
@@ -44,13 +49,13 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(const float* __restrict__
             Bs[buf][j * mma::LDK + kb] = rb[e];
         }
     };
-    const int nk = (K + mma::KC - 1) / mma::KC;
-    load(0);
+    const int nk = (K - k_lo + mma::KC - 1) / mma::KC;
+    load(k_lo);
     for (int kc = 0; kc < nk; ++kc) {
         const int buf = kc & 1;
         store(buf);
         __syncthreads();
-        if (kc + 1 < nk) load((kc + 1) * mma::KC);
+        if (kc + 1 < nk) load(k_lo + (kc + 1) * mma::KC);
         mma::chunk16<2, 2, false, true>(As[buf], mma::LDK, Bs[buf], mma::LDK, 32 * (wave >> 1), 32 * (wave & 1), acc, lane);
     }
     mma::drain();
@@ -102,20 +107,64 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ X
 
 constexpr int COLSUM_SLABS = 256;
 
-}  // namespace
+// C[i][j] = sum over the layers, in order, of partial[layer][i][j] (+ bias[j]) (ReLU)
+__global__ __launch_bounds__(256) void splitk_sum_kernel(const float* __restrict__ partial, float* __restrict__ C, long ldc, int M,
+                                                         int N, int layers, const float* __restrict__ bias, int relu) {
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (long)M * N) return;
+    float s = 0.f;
+    for (int l = 0; l < layers; ++l) s += partial[(long)l * M * N + e];
+    const int col = (int)(e % N);
+    if (bias) s += bias[col];
+    if (relu) s = fmaxf(s, 0.f);
+    C[(e / N) * ldc + col] = s;
+}
 
-extern "C" int dsspk_gemm(void* stream, const float* A, long a_rs, long a_cs, const float* B, long b_rs, long b_cs,
-                          float* C, long ldc, int M, int N, int K, const float* bias, int relu) {
-    if (!A || !B || !C || M < 1 || N < 1 || K < 1) return -1;
-    dim3 grid(ceil_div(N, BN), ceil_div(M, BM));
-    hipStream_t s = (hipStream_t)stream;
+int launch_gemm(hipStream_t s, const float* A, long a_rs, long a_cs, const float* B, long b_rs, long b_cs, float* C, long ldc,
+                int M, int N, int K, const float* bias, int relu, int layers) {
+    const int chunks = ceil_div(K, mma::KC);
+    const int k_per_layer = ceil_div(chunks, layers) * mma::KC;
+    dim3 grid(ceil_div(N, BN), ceil_div(M, BM), ceil_div(K, k_per_layer));
     const bool ak = a_cs == 1, bn = b_cs == 1;
-#define GO(AK, BNF) hipLaunchKernelGGL((gemm_kernel<AK, BNF>), grid, dim3(THREADS), 0, s, A, a_rs, a_cs, B, b_rs, b_cs, C, ldc, M, N, K, bias, relu)
+#define GO(AK, BNF) hipLaunchKernelGGL((gemm_kernel<AK, BNF>), grid, dim3(THREADS), 0, s, A, a_rs, a_cs, B, b_rs, b_cs, C, ldc, M, N, K, bias, relu, k_per_layer)
     if (ak && bn) GO(true, true);
     else if (ak) GO(true, false);
     else if (bn) GO(false, true);
     else GO(false, false);
 #undef GO
+    return (int)grid.z;
+}
+
+}  // namespace
+
+extern "C" int dsspk_gemm(void* stream, const float* A, long a_rs, long a_cs, const float* B, long b_rs, long b_cs,
+                          float* C, long ldc, int M, int N, int K, const float* bias, int relu) {
+    if (!A || !B || !C || M < 1 || N < 1 || K < 1) return -1;
+    launch_gemm((hipStream_t)stream, A, a_rs, a_cs, B, b_rs, b_cs, C, ldc, M, N, K, bias, relu, 1);
+    return DSSPK_LAUNCH_RC();
+}
+
+// Layers worth splitting K into (K of 1024 and more, fewer than 128 output tiles): enough workgroups to cover the
+// chip, at least 8 k-chunks of work per layer.
+extern "C" int dsspk_gemm_splitk_layers(int M, int N, int K) {
+    if (M < 1 || N < 1 || K < 1) return 0;
+    const int tiles = ceil_div(N, BN) * ceil_div(M, BM), chunks = ceil_div(K, mma::KC);
+    if (tiles >= 128 || chunks < 64) return 1;
+    const int want = ceil_div(384, tiles), most = chunks / 8;
+    const int layers = want < most ? want : most;
+    // as launched: the last layers may be empty once k_per_layer is rounded to whole chunks
+    return ceil_div(K, ceil_div(chunks, layers) * mma::KC);
+}
+
+extern "C" int dsspk_gemm_splitk(void* stream, const float* A, long a_rs, long a_cs, const float* B, long b_rs, long b_cs,
+                                 float* C, long ldc, int M, int N, int K, const float* bias, int relu, float* scratch, int layers) {
+    if (!A || !B || !C || M < 1 || N < 1 || K < 1 || layers < 1) return -1;
+    if (layers == 1) return dsspk_gemm(stream, A, a_rs, a_cs, B, b_rs, b_cs, C, ldc, M, N, K, bias, relu);
+    if (!scratch) return -1;
+    hipStream_t s = (hipStream_t)stream;
+    const int launched = launch_gemm(s, A, a_rs, a_cs, B, b_rs, b_cs, scratch, N, M, N, K, nullptr, 0, layers);
+    const long n = (long)M * N;
+    hipLaunchKernelGGL(splitk_sum_kernel, dim3((unsigned)ceil_div(n, 256L)), dim3(256), 0, s, scratch, C, ldc, M, N, launched, bias, relu);
     return DSSPK_LAUNCH_RC();
 }
 

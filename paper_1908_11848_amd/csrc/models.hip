@@ -42,7 +42,7 @@ struct Plan {
     std::vector<Tens> tens;
 
     // common tail
-    size_t logits = 0, dlogits = 0, colsum_scratch = 0, wg_scratch = 0, wg_scratch2 = 0, bn_scratch = 0, bn_scratch2 = 0, tot_a = 0, tot_b = 0;
+    size_t logits = 0, dlogits = 0, fc_scratch = 0, colsum_scratch = 0, wg_scratch = 0, wg_scratch2 = 0, bn_scratch = 0, bn_scratch2 = 0, tot_a = 0, tot_b = 0;
     // MLP
     size_t mlp_a1 = 0, mlp_da1 = 0;
     // AlexNet-style
@@ -142,6 +142,8 @@ struct Plan {
         logits = a.floats((size_t)m * classes);
         dlogits = a.floats((size_t)m * classes);
         tens.push_back({2, logits, (int64_t)m * classes});
+        // split-K scratch of the wide fully connected forward product (3136 -> 384)
+        fc_scratch = a.floats(id == DSSP_MODEL_ALEXNET_DS ? (size_t)dsspk_gemm_splitk_layers(m, 384, 3136) * m * 384 : 1);
         colsum_scratch = a.floats(id == DSSP_MODEL_ALEXNET_DS ? dsspk_colsum_scratch_floats((long)m * 32 * 32, 64) + 1 : 1);
         wg_scratch = a.floats(wg ? wg : 1);
         wg_scratch2 = a.floats(is_resnet(id) && wg ? wg : 1);   // d-filter partial sums alternate between the two
@@ -166,7 +168,7 @@ int step_mlp(Plan* P, char* ws, void* s, const float* x, const int32_t* y, const
     float* a1 = (float*)(ws + P->mlp_a1); float* da1 = (float*)(ws + P->mlp_da1);
     float* z = (float*)(ws + P->logits); float* dz = (float*)(ws + P->dlogits);
     const int64_t w1 = 0, b1 = 3072 * 256, w2 = b1 + 256, b2 = w2 + 256 * (int64_t)C;
-    RUN(dsspk_gemm(s, x, 3072, 1, w + w1, 256, 1, a1, 256, m, 256, 3072, w + b1, 1));
+    RUN(dsspk_gemm(s, x, 3072, 1, w + w1, 256, 1, a1, 256, m, 256, 3072, w + b1, 1));   // (split-K: one more launch, and this net is bound by launches)
     RUN(dsspk_gemm(s, a1, 256, 1, w + w2, C, 1, z, C, m, C, 256, w + b2, 0));
     RUN(dsspk_softmax_xent(s, z, y, dz, loss, m, C));
     RUN(dsspk_gemm(s, a1, 1, 256, dz, C, 1, g + w2, C, 256, C, m, nullptr, 0));          // dW2 = a1^T dz
@@ -192,7 +194,8 @@ int step_alexnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, c
     RUN(dsspk_maxpool_fwd(s, a1, p1, arg1, m, 32, 32, 64));
     RUN(dsspk_conv_fwd(s, p1, w + cw2, w + cb2, a2, m, 15, 15, 64, 64, 5, 5, 1, 2, 1, nullptr));
     RUN(dsspk_maxpool_fwd(s, a2, p2, arg2, m, 15, 15, 64));
-    RUN(dsspk_gemm(s, p2, 3136, 1, w + fw1, 384, 1, a3, 384, m, 384, 3136, w + fb1, 1));
+    RUN(dsspk_gemm_splitk(s, p2, 3136, 1, w + fw1, 384, 1, a3, 384, m, 384, 3136, w + fb1, 1, F(P->fc_scratch),
+                          dsspk_gemm_splitk_layers(m, 384, 3136)));
     RUN(dsspk_gemm(s, a3, 384, 1, w + fw2, 192, 1, a4, 192, m, 192, 384, w + fb2, 1));
     RUN(dsspk_gemm(s, a4, 192, 1, w + fw3, C, 1, z, C, m, C, 192, w + fb3, 0));
     RUN(dsspk_softmax_xent(s, z, y, dz, loss, m, C));

@@ -89,6 +89,20 @@ def test_fc_forward_backward(oracle_nn, m, n_in, n_out):
     yr = empty((m, n_out))
     rc(L.dsspk_gemm(s, X.data_ptr(), n_in, 1, W.data_ptr(), n_out, 1, yr.data_ptr(), n_out, m, n_out, n_in, Bv.data_ptr(), 1))
     assert rel_l2(host(yr), np.maximum(yo, 0)) < TOL
+    # the same forward product with the reduction index split over layers of workgroups (few output tiles, long K)
+    layers = L.dsspk_gemm_splitk_layers(m, n_out, n_in)
+    assert layers >= 1 and (layers > 1) == (n_in >= 3072)
+    for lay in sorted({layers, 1, 3}):
+        if lay * 16 > n_in and lay > 1:
+            continue
+        scratch = empty(lay * m * n_out)
+        ys = empty((m, n_out))
+        rc(L.dsspk_gemm_splitk(s, X.data_ptr(), n_in, 1, W.data_ptr(), n_out, 1, ys.data_ptr(), n_out, m, n_out, n_in,
+                               Bv.data_ptr(), 1, scratch.data_ptr(), lay))
+        assert rel_l2(host(ys), np.maximum(yo, 0)) < TOL
+    if layers > 1:
+        assert L.dsspk_gemm_splitk(s, X.data_ptr(), n_in, 1, W.data_ptr(), n_out, 1, ys.data_ptr(), n_out, m, n_out, n_in,
+                                   Bv.data_ptr(), 1, None, layers) == -1
 
 
 @pytest.mark.parametrize("M,N", [(1, 1), (1024, 64), (1025, 64), (131072, 64), (28800, 64), (5000, 100)])
