@@ -186,6 +186,12 @@ def test_resnet8_step_and_50_updates(oracle_nn):
     log, _ = em.run(d, total=50)
     assert log == out["log"] and np.array_equal(em.weights(), w_gpu)
     em.close()
+    # workers dealt onto the streams by their push rates, as the benchmark does: same schedule, same bits
+    em = Emulation(model, K, 3, 12, 0.05, w0, batch, 100, xs, ys, rates=[1.0 / float(np.mean(row)) for row in d])
+    assert sorted(set(em.lane_of)) == list(range(min(K, em.hardware_queues)))
+    log, _ = em.run(d, total=50, fused_pull=True)
+    assert log == out["log"] and np.array_equal(em.weights(), w_gpu)
+    em.close()
     # the applies on a stream of the server's own instead of the pushers': same schedule, same bits
     for fused in (False, True):
         em = Emulation(model, K, 3, 12, 0.05, w0, batch, 100, xs, ys, server_stream=True)
