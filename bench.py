@@ -48,7 +48,7 @@ def main():
     ap.add_argument("--worker-streams", type=int, default=WORKER_STREAMS)
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        raise SystemExit("bench.py: this build emulates the K workers on ONE GPU; run it with --gpus 1 "
+        raise SystemExit("bench.py: the K workers are emulated on ONE GPU; run it with --gpus 1 "
                          "(no multi-GPU figure exists)")
     import torch
     from paper_1908_11848_amd import binding as B, inputs
