@@ -15,21 +15,21 @@
 #include "../../include/dssp_kernels.h"
 
 // Specialised 3x3 / stride 1 / Cin = Cout kernels (k_conv3x3.hip); -2 = shape not covered.
-int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial,
+int conv3x3_tiled(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial,
                    int N, int HW, int C, bool transposed);
-int conv3x3_direct_stat_parts(int N, int HW, int C);
-int conv3x3_direct_dgrad_post(hipStream_t s, const float* dy, const float* w, const float* add, float* dz,
+int conv3x3_tiled_stat_parts(int N, int HW, int C);
+int conv3x3_tiled_dgrad_post(hipStream_t s, const float* dy, const float* w, const float* add, float* dz,
                               const float* mask_src, const float* xc, const float* stats, float* records, int N, int HW, int C);
-int conv3x3_direct_prebn(hipStream_t s, const float* src, const float* records, int in_parts, const float* gamma,
+int conv3x3_tiled_prebn(hipStream_t s, const float* src, const float* records, int in_parts, const float* gamma,
                          const float* beta, float eps, const float* shortcut, float* act_out, float* stats_out,
                          const float* w, float* dst, float* bn_partial, int N, int HW, int C);
-int wgrad3x3_direct_parts(int N, int HW, int C);
-int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C, const jobs::TotalsJob& tj);
-int conv3x3_direct_dgrad_bn(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
+int wgrad3x3_tiled_parts(int N, int HW, int C);
+int wgrad3x3_tiled(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C, const jobs::TotalsJob& tj);
+int conv3x3_tiled_dgrad_bn(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
                             const float* totals, float* dx_out, const float* w, const float* add, float* out,
                             const float* mask_src, const float* xc_post, const float* stats_post, float* records,
                             const float* red_partial, float* red_dw, int red_E, int red_chunks, int N, int HW, int C);
-int conv3x3_direct_dgrad_bn_wgrad(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
+int conv3x3_tiled_dgrad_bn_wgrad(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
                                   const float* totals, const float* w, const float* add, float* out,
                                   const float* xc_post, const float* stats_post, float* records,
                                   const float* x_in, float* partial, const float* red_partial, float* red_dw, int red_E,
@@ -472,7 +472,7 @@ int launch_igemm(hipStream_t s, const float* src, const float* w, const float* b
 }  // namespace
 
 extern "C" int dsspk_conv_fwd_stat_parts(int N, int H, int W, int Cin, int Cout, int KH, int KW, int stride, int pad) {
-    if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) return conv3x3_direct_stat_parts(N, H, Cin);
+    if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) return conv3x3_tiled_stat_parts(N, H, Cin);
     return 0;
 }
 
@@ -483,7 +483,7 @@ extern "C" int dsspk_conv_fwd(void* stream, const float* x, const float* w, cons
     if (!x || !w || !y || !geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
     if (bn_partial && (bias || relu || dsspk_conv_fwd_stat_parts(N, H, W, Cin, Cout, KH, KW, stride, pad) == 0)) return -1;
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W && !bias && !relu) {
-        const int rc = conv3x3_direct((hipStream_t)stream, x, w, nullptr, y, bn_partial, N, H, Cin, false);
+        const int rc = conv3x3_tiled((hipStream_t)stream, x, w, nullptr, y, bn_partial, N, H, Cin, false);
         if (rc != -2) return rc;
     }
     if (Cin % 16 == 0) return launch_igemm<false, true>((hipStream_t)stream, x, w, bias, nullptr, y, g, relu);
@@ -494,8 +494,8 @@ extern "C" int dsspk_conv_fwd_prebn(void* stream, const float* src, const float*
                                     const float* beta, float eps, const float* shortcut, float* act_out, float* stats_out,
                                     const float* w, float* y, float* bn_partial, int N, int H, int C) {
     if (!src || !records || !gamma || !beta || !act_out || !stats_out || !w || !y || N < 1) return -1;
-    if (conv3x3_direct_stat_parts(N, H, C) == 0) return -1;
-    const int rc = conv3x3_direct_prebn((hipStream_t)stream, src, records, in_parts, gamma, beta, eps, shortcut, act_out, stats_out,
+    if (conv3x3_tiled_stat_parts(N, H, C) == 0) return -1;
+    const int rc = conv3x3_tiled_prebn((hipStream_t)stream, src, records, in_parts, gamma, beta, eps, shortcut, act_out, stats_out,
                                         w, y, bn_partial, N, H, C);
     return rc == -2 ? -1 : rc;
 }
@@ -504,7 +504,7 @@ extern "C" int dsspk_conv_bwd_data_post(void* stream, const float* dy, const flo
                                         const float* mask_src, const float* xc, const float* stats, float* records,
                                         int N, int H, int C) {
     if (!dy || !w || !dz || !mask_src || !xc || !stats || !records || N < 1) return -1;
-    const int rc = conv3x3_direct_dgrad_post((hipStream_t)stream, dy, w, add, dz, mask_src, xc, stats, records, N, H, C);
+    const int rc = conv3x3_tiled_dgrad_post((hipStream_t)stream, dy, w, add, dz, mask_src, xc, stats, records, N, H, C);
     return rc == -2 ? -1 : rc;
 }
 
@@ -514,7 +514,7 @@ extern "C" int dsspk_conv_bwd_data(void* stream, const float* dy, const float* w
     if (!dy || !w || !dx || !geom(f, N, H, W, Cin, Cout, KH, KW, stride, pad)) return -1;
     if (Cout % 16) return -1;
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
-        const int rc = conv3x3_direct((hipStream_t)stream, dy, w, add, dx, nullptr, N, H, Cin, true);
+        const int rc = conv3x3_tiled((hipStream_t)stream, dy, w, add, dx, nullptr, N, H, Cin, true);
         if (rc != -2) return rc;
     }
     ConvGeom g = f;                       // rows: input pixels; gathered tensor: dy
@@ -530,24 +530,24 @@ extern "C" size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, 
     const int stages = wgrad_stages(g, gy);
     long chunks = ceil_div(g.M, 64L * stages);
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
-        const long parts = wgrad3x3_direct_parts(N, H, Cin);
+        const long parts = wgrad3x3_tiled_parts(N, H, Cin);
         if (parts > chunks) chunks = parts;
     }
     return (size_t)chunks * KH * KW * Cin * Cout;
 }
 
 // Stage 1 of the d-filter convolution: partial[chunk][KH*KW*Cin*Cout] in scratch, *chunks_out chunks.
-// tj.blocks > 0 asks the kernel to carry the batch-norm sums job (only the direct 3x3 and the tile kernels can).
+// tj.blocks > 0 asks the kernel to carry the batch-norm sums job (only the specialised 3x3 and the tile kernels can).
 static int wgrad_stage1(hipStream_t s, const float* x, const float* dy, float* scratch, const ConvGeom& g, int N, int H, int W,
                         int Cin, int Cout, int KH, int KW, int stride, int pad, const jobs::TotalsJob& tj, int* chunks_out) {
     if (Cout != 16 && Cout != 32 && Cout != 64) return -1;
     const bool vec = Cin % 16 == 0;
     const int rows_total = KH * KW * Cin;
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
-        const int parts = wgrad3x3_direct_parts(N, H, Cin);
+        const int parts = wgrad3x3_tiled_parts(N, H, Cin);
         if (parts > 0) {
             *chunks_out = parts;
-            return wgrad3x3_direct(s, x, dy, scratch, N, H, Cin, tj);
+            return wgrad3x3_tiled(s, x, dy, scratch, N, H, Cin, tj);
         }
     }
     const int gy = vec ? KH * KW : 1;
@@ -625,13 +625,13 @@ extern "C" int dsspk_conv_bwd_data_bn(void* stream, const float* dz, const float
         return -1;
     if (out == dz || dx == dz || dx == out) return -1;
     if (red_partial && (!red_dw || red_E < 4 || red_E % 4 || red_chunks < 1)) return -1;
-    const int rc = conv3x3_direct_dgrad_bn((hipStream_t)stream, dz, xc, stats, gamma, totals, dx, w, add, out, mask_src, xc_post,
+    const int rc = conv3x3_tiled_dgrad_bn((hipStream_t)stream, dz, xc, stats, gamma, totals, dx, w, add, out, mask_src, xc_post,
                                            stats_post, records, red_partial, red_dw, red_E, red_chunks, N, H, C);
     return rc == -2 ? -1 : rc;
 }
 
 extern "C" int dsspk_conv_bwd_fused_chunks(int N, int H, int C) {
-    if ((C == 16 && H == 32) || (C == 32 && H == 16)) return wgrad3x3_direct_parts(N, H, C);
+    if ((C == 16 && H == 32) || (C == 32 && H == 16)) return wgrad3x3_tiled_parts(N, H, C);
     return 0;
 }
 
@@ -646,7 +646,7 @@ extern "C" int dsspk_conv_bwd_data_bn_wgrad(void* stream, const float* dz, const
     if (out == dz || partial == red_partial) return -1;
     if (red_partial && (!red_dw || red_E < 4 || red_E % 4 || red_chunks < 1)) return -1;
     if (dsspk_conv_bwd_fused_chunks(N, H, C) == 0) return -1;
-    const int rc = conv3x3_direct_dgrad_bn_wgrad((hipStream_t)stream, dz, xc, stats, gamma, totals, w, add, out, xc_post,
+    const int rc = conv3x3_tiled_dgrad_bn_wgrad((hipStream_t)stream, dz, xc, stats, gamma, totals, w, add, out, xc_post,
                                                  stats_post, records, x_in, partial, red_partial, red_dw, red_E, red_chunks, N, H, C);
     return rc == -2 ? -1 : rc;
 }

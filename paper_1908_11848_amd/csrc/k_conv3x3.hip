@@ -617,7 +617,7 @@ int launch(hipStream_t s, const float* src, const float* w, const float* add, fl
 
 // dst = conv(src) (+ add, element-wise, if add != NULL).  Returns -2 if the shape is not one of the
 // specialised ones (the caller then uses the generic kernel).
-int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial,
+int conv3x3_tiled(hipStream_t s, const float* src, const float* w, const float* add, float* dst, float* bn_partial,
                    int N, int HW, int C, bool transposed) {
     if (C == 16 && HW == 32) return transposed ? launch<16, 32, 8, 1, true>(s, src, w, add, dst, bn_partial, N) : launch<16, 32, 8, 1, false>(s, src, w, add, dst, bn_partial, N);
     if (C == 32 && HW == 16) return transposed ? launch<32, 16, 8, 1, true>(s, src, w, add, dst, bn_partial, N) : launch<32, 16, 8, 1, false>(s, src, w, add, dst, bn_partial, N);
@@ -627,7 +627,7 @@ int conv3x3_direct(hipStream_t s, const float* src, const float* w, const float*
 
 // Forward convolution of a = ReLU(BN(src) (+ shortcut)), see PreBn.  in_parts: number of equal-sized
 // statistics records of src in `records` (as emitted by the forward kernel for the same shape).
-int conv3x3_direct_prebn(hipStream_t s, const float* src, const float* records, int in_parts, const float* gamma,
+int conv3x3_tiled_prebn(hipStream_t s, const float* src, const float* records, int in_parts, const float* gamma,
                          const float* beta, float eps, const float* shortcut, float* act_out, float* stats_out,
                          const float* w, float* dst, float* bn_partial, int N, int HW, int C) {
     PreBn pre;
@@ -656,7 +656,7 @@ int conv3x3_direct_prebn(hipStream_t s, const float* src, const float* records, 
 
 // d-input of the convolution (+ add) followed, in the same kernel, by the ReLU mask and the record sums of the
 // batch norm that comes next in the backward direction, see PostBn.
-int conv3x3_direct_dgrad_post(hipStream_t s, const float* dy, const float* w, const float* add, float* dz,
+int conv3x3_tiled_dgrad_post(hipStream_t s, const float* dy, const float* w, const float* add, float* dz,
                               const float* mask_src, const float* xc, const float* stats, float* records, int N, int HW, int C) {
     PostBn post;
     post.mask_src = mask_src; post.xc = xc; post.stats = stats; post.records = records;
@@ -666,9 +666,9 @@ int conv3x3_direct_dgrad_post(hipStream_t s, const float* dy, const float* w, co
     return -2;
 }
 
-// d-input convolution of dx = batch-norm backward of dz (see BwdBn), with the epilogue of conv3x3_direct_dgrad_post;
+// d-input convolution of dx = batch-norm backward of dz (see BwdBn), with the epilogue of conv3x3_tiled_dgrad_post;
 // optionally carries the second stage of an earlier d-filter convolution (red_partial != NULL).
-int conv3x3_direct_dgrad_bn(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
+int conv3x3_tiled_dgrad_bn(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
                             const float* totals, float* dx_out, const float* w, const float* add, float* out,
                             const float* mask_src, const float* xc_post, const float* stats_post, float* records,
                             const float* red_partial, float* red_dw, int red_E, int red_chunks, int N, int HW, int C) {
@@ -689,9 +689,9 @@ int conv3x3_direct_dgrad_bn(hipStream_t s, const float* dz, const float* xc, con
     return -2;
 }
 
-// conv3x3_direct_dgrad_bn with the d-filter convolution of the same layer in the same kernel (see WgradFused);
+// conv3x3_tiled_dgrad_bn with the d-filter convolution of the same layer in the same kernel (see WgradFused);
 // dx is not stored.  Returns -2 for shapes the fused form does not cover (then the two-kernel form applies).
-int conv3x3_direct_dgrad_bn_wgrad(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
+int conv3x3_tiled_dgrad_bn_wgrad(hipStream_t s, const float* dz, const float* xc, const float* stats, const float* gamma,
                                   const float* totals, const float* w, const float* add, float* out,
                                   const float* xc_post, const float* stats_post, float* records,
                                   const float* x_in, float* partial, const float* red_partial, float* red_dw, int red_E,
@@ -716,7 +716,7 @@ int conv3x3_direct_dgrad_bn_wgrad(hipStream_t s, const float* dz, const float* x
 
 // Number of per-workgroup statistics records (tiles of equal size) the forward kernel emits, 0 if the
 // shape is not covered by it.
-int conv3x3_direct_stat_parts(int N, int HW, int C) {
+int conv3x3_tiled_stat_parts(int N, int HW, int C) {
     if (C == 16 && HW == 32) return N * 4;
     if (C == 32 && HW == 16) return N * 2;
     if (C == 64 && HW == 8) return N;
@@ -933,14 +933,14 @@ int launch_wgrad(hipStream_t s, const float* x, const float* dy, float* partial,
 constexpr int WIDE_IMGS = 2;          // images per workgroup of the last stage's d-filter kernel
 
 // Number of partial results the specialised d-filter kernel writes, 0 if the shape is not covered.
-int wgrad3x3_direct_parts(int N, int HW, int C) {
+int wgrad3x3_tiled_parts(int N, int HW, int C) {
     if (C == 16 && HW == 32) return N * 4;
     if (C == 32 && HW == 16) return N * 2;
     if (C == 64 && HW == 8) return (N + WIDE_IMGS - 1) / WIDE_IMGS;
     return 0;
 }
 
-int wgrad3x3_direct(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C, const jobs::TotalsJob& tj) {
+int wgrad3x3_tiled(hipStream_t s, const float* x, const float* dy, float* partial, int N, int HW, int C, const jobs::TotalsJob& tj) {
     if (C == 16 && HW == 32) return launch_wgrad<16, 32, 8>(s, x, dy, partial, N, tj);
     if (C == 32 && HW == 16) return launch_wgrad<32, 16, 8>(s, x, dy, partial, N, tj);
     if (C == 64 && HW == 8) return launch_wgrad_wide<WIDE_IMGS>(s, x, dy, partial, N, tj);

@@ -233,7 +233,7 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
     RUN(dsspk_bn_fwd(s, F(P->stem_c), w + P->stem_g, w + P->stem_b, F(P->stem_a), F(P->stem_st), bscr,
                      (long)m * 1024, 16, eps, 1, 0, nullptr, 0, 0, 0, 0));
     // Statistics records ping-pong between two buffers: conv1 writes recA, conv2 reads recA and writes recB,
-    // the next block's conv1 reads recB.  A "regular" block (stride 1, same width, shape covered by the direct
+    // the next block's conv1 reads recB.  A "regular" block (stride 1, same width, shape covered by the specialised
     // kernels) has its two batch norms folded into the loaders of the convolutions that consume them:
     //   conv1 [+ BN2/shortcut/ReLU of the previous block in its loader]  ->  conv2 [+ BN1/ReLU in its loader]
     // and only the last block of a run materialises its output with the stand-alone BN kernels.
@@ -283,7 +283,7 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
     float *g0 = F(P->G[0]), *g1 = F(P->G[1]), *g2 = F(P->G[2]);     // g0: gradient w.r.t. the current block output
     RUN(dsspk_gap_bwd(s, F(P->dpooled), g0, m, 64, 64));
     // Per convolution layer the backward pass is  BN backward -> d-input convolution -> d-filter convolution.
-    // Where the direct 3x3 kernels apply, and the gradient arrives already masked with sum records (written by the
+    // Where the specialised 3x3 kernels apply, and the gradient arrives already masked with sum records (written by the
     // epilogue of the d-input convolution before it), these collapse (regular_layer below):
     //   stages 1-2: ONE kernel - BN backward in its loader, d-input convolution, ReLU mask + sum records of the
     //               next batch norm in its epilogue, and the d-filter partial sums from the same LDS tiles (dx is
@@ -358,7 +358,7 @@ int step_resnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, co
         }
         // ---- BN1 + conv1: g2 = dz1 -> g1 = d conv1 output; d-input (+ dz2 through an identity shortcut) = gradient
         //      w.r.t. the block's input, which is the previous block's (or the stem's) post-ReLU output: mask +
-        //      records of ITS batch norm in the same kernel where the direct kernel applies
+        //      records of ITS batch norm in the same kernel where the specialised kernel applies
         if (fused1) {
             const float* pc = bi ? F(P->blocks[bi - 1].c2) : F(P->stem_c);
             const float* pst = bi ? F(P->blocks[bi - 1].st2) : F(P->stem_st);
