@@ -28,6 +28,8 @@ def workload(name):
     """-> dict(model, config, K, s_L, r_max, lr, batch, n_classes, pool)"""
     if name == "resnet110":
         return dict(model="resnet110", config=4, K=8, s_L=3, r_max=12, lr=0.05, batch=128, n_classes=100, pool=8)
+    if name == "resnet50":       # the paper's other residual network (Sec. V-A3), same 6n+2 family
+        return dict(model="resnet50", config=4, K=8, s_L=3, r_max=12, lr=0.05, batch=128, n_classes=100, pool=8)
     if name == "alexnet_ds":
         return dict(model="alexnet_ds", config=2, K=4, s_L=3, r_max=12, lr=0.001, batch=128, n_classes=10, pool=16)
     if name == "mlp":
@@ -121,7 +123,7 @@ def cpu_baseline(name, wl):
         dt = time.perf_counter() - t0
         return {"value": round(sample / dt, 3), "unit": "pushes/s", "cores": 1, "kind": "oracle",
                 "sample": "first %d pushes of the same schedule (numpy fp64 apply + snapshot copies)" % sample}
-    sample = {"resnet110": 3, "alexnet_ds": 16, "mlp": 200}[name]
+    sample = {"resnet110": 3, "resnet50": 6, "alexnet_ds": 16, "mlp": 200}[name]
     net = nn.make_net(wl["model"], wl["n_classes"])
     w0 = inputs.init_weights(B.dssp_model_segments(B.model_id(wl["model"]), wl["n_classes"]), wl["config"])
     xs, ys = inputs.batches(wl["config"], K, 1, wl["batch"], wl["n_classes"])

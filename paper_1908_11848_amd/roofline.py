@@ -249,7 +249,7 @@ def measure(workload, em):
     """(dominant kernel entry, list of the other entries).  The kernel with the largest share of GPU time in the
     ResNet-110 profile is the fused backward convolution kernel of the first stage; for the server stress it is the apply kernel."""
     allm = measure_all(em.dev, em.streams[0], em.n)
-    if workload == "resnet110":
+    if workload.startswith("resnet"):
         top = "conv_bwd_fused_32x32x16"
     elif workload == "alexnet_ds":
         case = _alexnet_conv2_case(em.dev)

@@ -208,7 +208,7 @@ def test_resnet8_step_and_50_updates(oracle_nn):
     em.close()
 
 
-@pytest.mark.parametrize("model,K,batch", [("resnet20", 4, 8), ("resnet110", 8, 8)])
+@pytest.mark.parametrize("model,K,batch", [("resnet20", 4, 8), ("resnet50", 4, 8), ("resnet110", 8, 8)])
 def test_resnet_deep_50_updates(oracle_nn, model, K, batch):
     """Deep ReLU networks at lr 0.05: the free-running 50-update trajectory is ill-conditioned (the
     oracle's own weights move by more than 1e-3 when w0 changes in the 7th digit), so (a) the strict

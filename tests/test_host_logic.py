@@ -146,6 +146,18 @@ def test_paradigm_sweep_in_virtual_time():
         assert res["BSP"]["staleness_max"] == 0 and res["SSP s=3"]["staleness_max"] <= 3
         assert res["SSP s=15"]["staleness_max"] <= 15 and res["DSSP (3,12)"]["staleness_max"] <= 15
         assert all(v["pushes"] == 100 * K for v in res.values())
+        # staleness histograms: one entry per OK; nothing beyond the paradigm's bound; the averaged SSP of DSSP's
+        # range (Sec. V-B) lies between SSP at the two ends, and DSSP keeps most OKs at or below its lower bound
+        for name, v in res.items():
+            h = v["staleness_hist"]
+            assert len(h) == v["staleness_max"] + 1 and h[-1] > 0
+            if name != "SSP s=3..15":            # (a mean of thirteen means, not the mean of the summed histogram)
+                assert abs(sum(k * c for k, c in enumerate(h)) / sum(h) - v["staleness_mean"]) < 1e-9
+        avg = res["SSP s=3..15"]
+        assert rate["SSP s=15"] >= avg["pushes_per_unit_time"] >= rate["SSP s=3"]
+        assert res["SSP s=3"]["staleness_mean"] <= avg["staleness_mean"] <= res["SSP s=15"]["staleness_mean"]
+        hd = res["DSSP (3,12)"]["staleness_hist"]
+        assert sum(hd[:4]) > 0.6 * sum(hd) and res["DSSP (3,12)"]["staleness_mean"] < avg["staleness_mean"]
 
 
 def test_workers_are_dealt_onto_streams_by_their_rates():
