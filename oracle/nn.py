@@ -300,6 +300,57 @@ class AlexNetDS(_Net):
         return loss, self.pack(G), trace
 
 
+class AlexNet3C(_Net):
+    """The paper's reduced AlexNet (Sec. V-A3: three convolutional and two fully connected layers; the paper
+    gives no widths, these are this repository's reading, on the pattern of the two-convolution network above):
+    conv5x5x64 - maxpool3s2 - conv5x5x64 - maxpool3s2 - conv3x3x128 - FC384 - FC classes.
+    Convolutions: stride 1, zero padding 2 (5x5) / 1 (3x3), bias, ReLU.  Pools: no padding, floor."""
+
+    def __init__(self, n_classes=10):
+        self.n_classes = n_classes
+
+    def segments(self):
+        return [("conv1.w", (5, 5, 3, 64)), ("conv1.b", (64,)),
+                ("conv2.w", (5, 5, 64, 64)), ("conv2.b", (64,)),
+                ("conv3.w", (3, 3, 64, 128)), ("conv3.b", (128,)),
+                ("fc1.w", (7 * 7 * 128, 384)), ("fc1.b", (384,)),
+                ("fc2.w", (384, self.n_classes)), ("fc2.b", (self.n_classes,))]
+
+    def loss_and_grad(self, w, x, y, tie_break=None):
+        tb = tie_break or {}
+        tol = self.ambig_tol
+        P = self.unpack(w)
+        x0 = _f64(x)
+        m = x0.shape[0]
+        z1 = conv2d_fwd(x0, P["conv1.w"], P["conv1.b"], 1, 2)
+        a1, act1 = relu_fwd(z1, tb.get(("relu", 0)), tol)
+        p1, arg1, gap1 = maxpool_fwd(a1, 3, 2, tb.get(("pool", 0)), tol)
+        z2 = conv2d_fwd(p1, P["conv2.w"], P["conv2.b"], 1, 2)
+        a2, act2 = relu_fwd(z2, tb.get(("relu", 1)), tol)
+        p2, arg2, gap2 = maxpool_fwd(a2, 3, 2, tb.get(("pool", 1)), tol)
+        z3 = conv2d_fwd(p2, P["conv3.w"], P["conv3.b"], 1, 1)
+        a3, act3 = relu_fwd(z3, tb.get(("relu", 2)), tol)
+        f0 = a3.reshape(m, -1)
+        z4 = fc_fwd(f0, P["fc1.w"], P["fc1.b"])
+        a4, act4 = relu_fwd(z4, tb.get(("relu", 3)), tol)
+        z5 = fc_fwd(a4, P["fc2.w"], P["fc2.b"])
+        loss, dz5 = softmax_xent(z5, y)
+        G = {}
+        da4, G["fc2.w"], G["fc2.b"] = fc_bwd(a4, P["fc2.w"], dz5)
+        df0, G["fc1.w"], G["fc1.b"] = fc_bwd(f0, P["fc1.w"], relu_bwd(da4, act4))
+        dp2, G["conv3.w"], G["conv3.b"] = conv2d_bwd(p2, P["conv3.w"], relu_bwd(df0.reshape(a3.shape), act3), 1, 1, True)
+        da2 = maxpool_bwd(dp2, arg2, a2.shape, 3, 2)
+        dp1, G["conv2.w"], G["conv2.b"] = conv2d_bwd(p1, P["conv2.w"], relu_bwd(da2, act2), 1, 2, True)
+        da1 = maxpool_bwd(dp1, arg1, a1.shape, 3, 2)
+        _, G["conv1.w"], G["conv1.b"] = conv2d_bwd(x0, P["conv1.w"], relu_bwd(da1, act1), 1, 2, True,
+                                                   need_dx=False)
+        trace = {("relu", 0): dict(z=z1, active=act1), ("relu", 1): dict(z=z2, active=act2),
+                 ("relu", 2): dict(z=z3, active=act3), ("relu", 3): dict(z=z4, active=act4),
+                 ("pool", 0): dict(x=a1, arg=arg1, gap=gap1), ("pool", 1): dict(x=a2, arg=arg2, gap=gap2),
+                 "logits": z5}
+        return loss, self.pack(G), trace
+
+
 class ResNetCifar(_Net):
     """6n+2-layer CIFAR ResNet (n = 18 gives ResNet-110): conv3x3(3->16)-BN-ReLU,
     three stages of n basic blocks with 16/32/64 channels (conv-BN-ReLU-conv-BN,
@@ -381,11 +432,13 @@ class ResNetCifar(_Net):
 
 
 def make_net(model, n_classes):
-    """model: 'mlp' | 'alexnet_ds' | 'resnet110' | 'resnet<6n+2>'."""
+    """model: 'mlp' | 'alexnet_ds' | 'alexnet_3c' | 'resnet110' | 'resnet<6n+2>'."""
     if model == "mlp":
         return MLP(n_classes=n_classes)
     if model == "alexnet_ds":
         return AlexNetDS(n_classes=n_classes)
+    if model == "alexnet_3c":
+        return AlexNet3C(n_classes=n_classes)
     if model.startswith("resnet"):
         depth = int(model[len("resnet"):])
         assert (depth - 2) % 6 == 0

@@ -111,6 +111,30 @@ def test_alexnet_against_torch_autograd(oracle_nn):
     assert rel(grad, back_to_flat(net, tp)) < 1e-12
 
 
+def test_alexnet_3conv_against_torch_autograd(oracle_nn):
+    net = oracle_nn.AlexNet3C(n_classes=10)
+    g = np.random.default_rng(5)
+    w = inputs.init_weights(seg_table(net), 2, jitter=0.1).astype(np.float64)
+    x = g.standard_normal((3, 32, 32, 3))
+    y = g.integers(0, 10, 3).astype(np.int32)
+    loss, grad, trace = net.loss_and_grad(w, x, y)
+    P = net.unpack(w)
+    tp = {n: t_param(P, n, conv=len(s) == 4, fc=len(s) == 2) for n, s in net.segments()}
+    h = torch.tensor(x).permute(0, 3, 1, 2)
+    h = F.max_pool2d(F.relu(F.conv2d(h, tp["conv1.w"], tp["conv1.b"], padding=2)), 3, 2)
+    h = F.max_pool2d(F.relu(F.conv2d(h, tp["conv2.w"], tp["conv2.b"], padding=2)), 3, 2)
+    h = F.relu(F.conv2d(h, tp["conv3.w"], tp["conv3.b"], padding=1))
+    h = h.permute(0, 2, 3, 1).reshape(3, -1)          # (h, w, c) flatten order
+    h = F.relu(F.linear(h, tp["fc1.w"], tp["fc1.b"]))
+    z = F.linear(h, tp["fc2.w"], tp["fc2.b"])
+    L = F.cross_entropy(z, torch.tensor(y, dtype=torch.long))
+    L.backward()
+    assert abs(loss - L.item()) < 1e-12
+    assert rel(trace["logits"], z.detach().numpy()) < 1e-13
+    assert rel(grad, back_to_flat(net, tp)) < 1e-12
+    assert net.n_params() == 4864 + 102464 + 73856 + 6272 * 384 + 384 + 3850
+
+
 @pytest.mark.parametrize("n", [1, 2])
 def test_resnet_against_torch_autograd(oracle_nn, n):
     net = oracle_nn.ResNetCifar(n=n, n_classes=11)
