@@ -32,6 +32,8 @@ def workload(name):
         return dict(model="resnet50", config=4, K=8, s_L=3, r_max=12, lr=0.05, batch=128, n_classes=100, pool=8)
     if name == "alexnet_ds":
         return dict(model="alexnet_ds", config=2, K=4, s_L=3, r_max=12, lr=0.001, batch=128, n_classes=10, pool=16)
+    if name == "alexnet_3c":     # Sec. V-A3's reduced AlexNet with three convolutional and two fully connected layers
+        return dict(model="alexnet_3c", config=2, K=4, s_L=3, r_max=12, lr=0.001, batch=128, n_classes=10, pool=16)
     if name == "mlp":
         return dict(model="mlp", config=1, K=4, s_L=3, r_max=4, lr=0.01, batch=32, n_classes=10, pool=50)
     if name == "stress":
@@ -123,7 +125,7 @@ def cpu_baseline(name, wl):
         dt = time.perf_counter() - t0
         return {"value": round(sample / dt, 3), "unit": "pushes/s", "cores": 1, "kind": "oracle",
                 "sample": "first %d pushes of the same schedule (numpy fp64 apply + snapshot copies)" % sample}
-    sample = {"resnet110": 3, "resnet50": 6, "alexnet_ds": 16, "mlp": 200}[name]
+    sample = {"resnet110": 3, "resnet50": 6, "alexnet_ds": 16, "alexnet_3c": 16, "mlp": 200}[name]
     net = nn.make_net(wl["model"], wl["n_classes"])
     w0 = inputs.init_weights(B.dssp_model_segments(B.model_id(wl["model"]), wl["n_classes"]), wl["config"])
     xs, ys = inputs.batches(wl["config"], K, 1, wl["batch"], wl["n_classes"])

@@ -58,6 +58,9 @@ enum {
     DSSP_MODEL_NONE = 0,        /* flat vector only: push / pull / clock, no worker_step */
     DSSP_MODEL_MLP = 1,         /* 3072 - 256 - n_classes, ReLU */
     DSSP_MODEL_ALEXNET_DS = 2,  /* conv5x5x64, maxpool3s2, conv5x5x64, maxpool3s2, FC384, FC192, FC n_classes */
+    DSSP_MODEL_ALEXNET_3C = 3,  /* Sec. V-A3's reduced AlexNet, three convolutional and two fully connected layers (widths:
+                                   this library's reading): conv5x5x64, maxpool3s2, conv5x5x64, maxpool3s2, conv3x3x64,
+                                   FC384, FC n_classes */
     DSSP_MODEL_RESNET110 = 110  /* 3 stages x 18 basic blocks, 16/32/64 channels, BN, parameter-free shortcuts */
 };
 

@@ -303,7 +303,7 @@ class AlexNetDS(_Net):
 class AlexNet3C(_Net):
     """The paper's reduced AlexNet (Sec. V-A3: three convolutional and two fully connected layers; the paper
     gives no widths, these are this repository's reading, on the pattern of the two-convolution network above):
-    conv5x5x64 - maxpool3s2 - conv5x5x64 - maxpool3s2 - conv3x3x128 - FC384 - FC classes.
+    conv5x5x64 - maxpool3s2 - conv5x5x64 - maxpool3s2 - conv3x3x64 - FC384 - FC classes.
     Convolutions: stride 1, zero padding 2 (5x5) / 1 (3x3), bias, ReLU.  Pools: no padding, floor."""
 
     def __init__(self, n_classes=10):
@@ -312,8 +312,8 @@ class AlexNet3C(_Net):
     def segments(self):
         return [("conv1.w", (5, 5, 3, 64)), ("conv1.b", (64,)),
                 ("conv2.w", (5, 5, 64, 64)), ("conv2.b", (64,)),
-                ("conv3.w", (3, 3, 64, 128)), ("conv3.b", (128,)),
-                ("fc1.w", (7 * 7 * 128, 384)), ("fc1.b", (384,)),
+                ("conv3.w", (3, 3, 64, 64)), ("conv3.b", (64,)),
+                ("fc1.w", (7 * 7 * 64, 384)), ("fc1.b", (384,)),
                 ("fc2.w", (384, self.n_classes)), ("fc2.b", (self.n_classes,))]
 
     def loss_and_grad(self, w, x, y, tie_break=None):

@@ -14,11 +14,11 @@ DSSP_OK, DSSP_EINVAL, DSSP_ESTATE, DSSP_EHIP, DSSP_ENOMEM = 0, -1, -2, -3, -4
 DSSP_MODEL_NONE, DSSP_MODEL_MLP, DSSP_MODEL_ALEXNET_DS, DSSP_MODEL_RESNET110 = 0, 1, 2, 110
 DSSP_S_L_NEVER_WAIT = 2**31 - 1
 
-MODEL_IDS = {"none": 0, "mlp": 1, "alexnet_ds": 2}
+MODEL_IDS = {"none": 0, "mlp": 1, "alexnet_ds": 2, "alexnet_3c": 3}
 
 
 def model_id(name):
-    """'mlp' | 'alexnet_ds' | 'resnet<6n+2>' | 'none' -> model id of the C ABI."""
+    """'mlp' | 'alexnet_ds' | 'alexnet_3c' | 'resnet<6n+2>' | 'none' -> model id of the C ABI."""
     if name in MODEL_IDS:
         return MODEL_IDS[name]
     if name.startswith("resnet"):

@@ -1,5 +1,6 @@
-// The three networks of the workloads as fixed launch sequences (internal, see model.hpp), and the
+// The networks of the workloads as fixed launch sequences (internal, see model.hpp), and the
 // host-only queries about their parameter vector and workspace.
+#include <algorithm>
 #include <cstdio>
 #include <vector>
 
@@ -48,6 +49,7 @@ struct Plan {
     // AlexNet-style
     size_t ax_a1 = 0, ax_p1 = 0, ax_arg1 = 0, ax_a2 = 0, ax_p2 = 0, ax_arg2 = 0, ax_a3 = 0, ax_a4 = 0;
     size_t ax_da4 = 0, ax_da3 = 0, ax_dp2 = 0, ax_da2 = 0, ax_dp1 = 0, ax_da1 = 0;
+    size_t ax_c3 = 0, ax_dc3 = 0;     // three-convolution variant: conv3 output (post-ReLU) and its gradient
     // ResNet
     std::vector<ResBlock> blocks;
     int64_t stem_w = 0, stem_g = 0, stem_b = 0, fc_w = 0, fc_b = 0;
@@ -105,6 +107,24 @@ struct Plan {
             tens.push_back({0, ax_a1, (int64_t)s32}); tens.push_back({0, ax_a2, (int64_t)s15});
             tens.push_back({0, ax_a3, (int64_t)m * 384}); tens.push_back({0, ax_a4, (int64_t)m * 192});
             tens.push_back({1, ax_arg1, (int64_t)s15}); tens.push_back({1, ax_arg2, (int64_t)s7});
+        } else if (id == DSSP_MODEL_ALEXNET_3C) {
+            conv_seg(5, 3, 64, true);
+            conv_seg(5, 64, 64, true);
+            conv_seg(3, 64, 64, true);
+            fc_seg(7 * 7 * 64, 384);
+            fc_seg(384, classes);
+            const size_t s32 = (size_t)m * 32 * 32 * 64, s15 = (size_t)m * 15 * 15 * 64, s7 = (size_t)m * 7 * 7 * 64, s7c = s7;
+            ax_a1 = a.floats(s32); ax_p1 = a.floats(s15); ax_arg1 = a.take(s15);
+            ax_a2 = a.floats(s15); ax_p2 = a.floats(s7); ax_arg2 = a.take(s7);
+            ax_c3 = a.floats(s7c); ax_a3 = a.floats((size_t)m * 384);
+            ax_da3 = a.floats((size_t)m * 384); ax_dc3 = a.floats(s7c); ax_dp2 = a.floats(s7);
+            ax_da2 = a.floats(s15); ax_dp1 = a.floats(s15); ax_da1 = a.floats(s32);
+            wg_need(m, 32, 3, 64, 5, 1, 2);
+            wg_need(m, 15, 64, 64, 5, 1, 2);
+            wg_need(m, 7, 64, 64, 3, 1, 1);
+            tens.push_back({0, ax_a1, (int64_t)s32}); tens.push_back({0, ax_a2, (int64_t)s15});
+            tens.push_back({0, ax_c3, (int64_t)s7c}); tens.push_back({0, ax_a3, (int64_t)m * 384});
+            tens.push_back({1, ax_arg1, (int64_t)s15}); tens.push_back({1, ax_arg2, (int64_t)s7});
         } else if (is_resnet(id)) {
             const int n = (id - 2) / 6;
             stem_w = conv_seg(3, 3, 16, false);
@@ -143,8 +163,13 @@ struct Plan {
         dlogits = a.floats((size_t)m * classes);
         tens.push_back({2, logits, (int64_t)m * classes});
         // split-K scratch of the wide fully connected forward product (3136 -> 384)
-        fc_scratch = a.floats(id == DSSP_MODEL_ALEXNET_DS ? (size_t)dsspk_gemm_splitk_layers(m, 384, 3136) * m * 384 : 1);
-        colsum_scratch = a.floats(id == DSSP_MODEL_ALEXNET_DS ? dsspk_colsum_scratch_floats((long)m * 32 * 32, 64) + 1 : 1);
+        fc_scratch = a.floats(id == DSSP_MODEL_ALEXNET_DS ? (size_t)dsspk_gemm_splitk_layers(m, 384, 3136) * m * 384
+                              : id == DSSP_MODEL_ALEXNET_3C ? (size_t)dsspk_gemm_splitk_layers(m, 384, 3136) * m * 384 : 1);
+        {
+            size_t cs = 1;
+            if (id == DSSP_MODEL_ALEXNET_DS || id == DSSP_MODEL_ALEXNET_3C) cs = dsspk_colsum_scratch_floats((long)m * 32 * 32, 64) + 1;
+            colsum_scratch = a.floats(cs);
+        }
         wg_scratch = a.floats(wg ? wg : 1);
         wg_scratch2 = a.floats(is_resnet(id) && wg ? wg : 1);   // d-filter partial sums alternate between the two
         bn_scratch = a.floats(bn ? bn : 1);
@@ -220,6 +245,51 @@ int step_alexnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, c
     RUN(dsspk_relu_bwd(s, da1, a1, (long)m * 32 * 32 * 64));
     RUN(dsspk_conv_bwd_weight(s, x, da1, g + cw1, scr, m, 32, 32, 3, 64, 5, 5, 1, 2));
     RUN(dsspk_colsum(s, da1, g + cb1, F(P->colsum_scratch), (long)m * 32 * 32, 64));
+    return 0;
+}
+
+// The reduced AlexNet with three convolutional and two fully connected layers (Sec. V-A3); the layers and kernels of
+// step_alexnet in a different order.
+int step_alexnet3(Plan* P, char* ws, void* s, const float* x, const int32_t* y, const float* w, float* g, float* loss, std::string& err) {
+    const int m = P->m, C = P->n_classes;
+    auto F = [&](size_t off) { return (float*)(ws + off); };
+    float *a1 = F(P->ax_a1), *p1 = F(P->ax_p1), *a2 = F(P->ax_a2), *p2 = F(P->ax_p2), *c3 = F(P->ax_c3), *a3 = F(P->ax_a3);
+    uint8_t *arg1 = (uint8_t*)(ws + P->ax_arg1), *arg2 = (uint8_t*)(ws + P->ax_arg2);
+    float *z = F(P->logits), *dz = F(P->dlogits), *da3 = F(P->ax_da3), *dc3 = F(P->ax_dc3), *dp2 = F(P->ax_dp2);
+    float *da2 = F(P->ax_da2), *dp1 = F(P->ax_dp1), *da1 = F(P->ax_da1), *scr = F(P->wg_scratch), *cscr = F(P->colsum_scratch);
+    const int64_t cw1 = 0, cb1 = 4800, cw2 = cb1 + 64, cb2 = cw2 + 102400, cw3 = cb2 + 64, cb3 = cw3 + 36864,
+                  fw1 = cb3 + 64, fb1 = fw1 + 3136 * 384, fw2 = fb1 + 384, fb2 = fw2 + 384 * (int64_t)C;
+    // forward
+    RUN(dsspk_conv_fwd(s, x, w + cw1, w + cb1, a1, m, 32, 32, 3, 64, 5, 5, 1, 2, 1, nullptr));
+    RUN(dsspk_maxpool_fwd(s, a1, p1, arg1, m, 32, 32, 64));
+    RUN(dsspk_conv_fwd(s, p1, w + cw2, w + cb2, a2, m, 15, 15, 64, 64, 5, 5, 1, 2, 1, nullptr));
+    RUN(dsspk_maxpool_fwd(s, a2, p2, arg2, m, 15, 15, 64));
+    RUN(dsspk_conv_fwd(s, p2, w + cw3, w + cb3, c3, m, 7, 7, 64, 64, 3, 3, 1, 1, 1, nullptr));
+    RUN(dsspk_gemm_splitk(s, c3, 3136, 1, w + fw1, 384, 1, a3, 384, m, 384, 3136, w + fb1, 1, F(P->fc_scratch),
+                          dsspk_gemm_splitk_layers(m, 384, 3136)));
+    RUN(dsspk_gemm(s, a3, 384, 1, w + fw2, C, 1, z, C, m, C, 384, w + fb2, 0));
+    RUN(dsspk_softmax_xent(s, z, y, dz, loss, m, C));
+    // backward
+    RUN(dsspk_gemm(s, a3, 1, 384, dz, C, 1, g + fw2, C, 384, C, m, nullptr, 0));
+    RUN(dsspk_colsum(s, dz, g + fb2, nullptr, m, C));
+    RUN(dsspk_gemm(s, dz, C, 1, w + fw2, 1, C, da3, 384, m, 384, C, nullptr, 0));
+    RUN(dsspk_relu_bwd(s, da3, a3, (long)m * 384));
+    RUN(dsspk_gemm(s, c3, 1, 3136, da3, 384, 1, g + fw1, 384, 3136, 384, m, nullptr, 0));
+    RUN(dsspk_colsum(s, da3, g + fb1, nullptr, m, 384));
+    RUN(dsspk_gemm(s, da3, 384, 1, w + fw1, 1, 384, dc3, 3136, m, 3136, 384, nullptr, 0));
+    RUN(dsspk_relu_bwd(s, dc3, c3, (long)m * 3136));
+    RUN(dsspk_conv_bwd_weight(s, p2, dc3, g + cw3, scr, m, 7, 7, 64, 64, 3, 3, 1, 1));
+    RUN(dsspk_colsum(s, dc3, g + cb3, cscr, (long)m * 7 * 7, 64));
+    RUN(dsspk_conv_bwd_data(s, dc3, w + cw3, nullptr, dp2, m, 7, 7, 64, 64, 3, 3, 1, 1));
+    RUN(dsspk_maxpool_bwd(s, dp2, arg2, da2, m, 15, 15, 64));
+    RUN(dsspk_relu_bwd(s, da2, a2, (long)m * 15 * 15 * 64));
+    RUN(dsspk_conv_bwd_weight(s, p1, da2, g + cw2, scr, m, 15, 15, 64, 64, 5, 5, 1, 2));
+    RUN(dsspk_colsum(s, da2, g + cb2, cscr, (long)m * 15 * 15, 64));
+    RUN(dsspk_conv_bwd_data(s, da2, w + cw2, nullptr, dp1, m, 15, 15, 64, 64, 5, 5, 1, 2));
+    RUN(dsspk_maxpool_bwd(s, dp1, arg1, da1, m, 32, 32, 64));
+    RUN(dsspk_relu_bwd(s, da1, a1, (long)m * 32 * 32 * 64));
+    RUN(dsspk_conv_bwd_weight(s, x, da1, g + cw1, scr, m, 32, 32, 3, 64, 5, 5, 1, 2));
+    RUN(dsspk_colsum(s, da1, g + cb1, cscr, (long)m * 32 * 32, 64));
     return 0;
 }
 
@@ -413,6 +483,7 @@ int step(Plan* P, int worker, hipStream_t stream, const float* x, const int32_t*
     char* ws = P->ws + (size_t)worker * P->per_worker;
     if (P->model_id == DSSP_MODEL_MLP) return step_mlp(P, ws, stream, x, y, w, g, loss, err);
     if (P->model_id == DSSP_MODEL_ALEXNET_DS) return step_alexnet(P, ws, stream, x, y, w, g, loss, err);
+    if (P->model_id == DSSP_MODEL_ALEXNET_3C) return step_alexnet3(P, ws, stream, x, y, w, g, loss, err);
     return step_resnet(P, ws, stream, x, y, w, g, loss, err);
 }
 

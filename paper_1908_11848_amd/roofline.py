@@ -251,7 +251,7 @@ def measure(workload, em):
     allm = measure_all(em.dev, em.streams[0], em.n)
     if workload.startswith("resnet"):
         top = "conv_bwd_fused_32x32x16"
-    elif workload == "alexnet_ds":
+    elif workload.startswith("alexnet"):
         case = _alexnet_conv2_case(em.dev)
         top = case[0]
         allm[top] = _entry(case, _time(case[4], em.streams[0]))

@@ -101,28 +101,30 @@ def test_mlp_config1_schedule_gradients_weights(oracle_nn):
 
 
 # ------------------------------------------------------------------ config 2 / 3: AlexNet-style
-def test_alexnet_step_gradient_batch128(oracle_nn):
+@pytest.mark.parametrize("model", ["alexnet_ds", "alexnet_3c"])
+def test_alexnet_step_gradient_batch128(oracle_nn, model):
     K = 4
-    net = oracle_nn.make_net("alexnet_ds", 10)
-    w0 = inputs.init_weights(segs_of("alexnet_ds", 10), 2, jitter=0.1)
+    net = oracle_nn.make_net(model, 10)
+    w0 = inputs.init_weights(segs_of(model, 10), 2, jitter=0.1)
     xs, ys = inputs.batches(2, K, 1, 128, 10)
-    em = Emulation("alexnet_ds", K, 3, 12, 0.001, w0, 128, 10, xs, ys)
+    em = Emulation(model, K, 3, 12, 0.001, w0, 128, 10, xs, ys)
     for p in range(K):
         B.dssp_pull(em.ctx, p, em.w_local[p])
         em.step(p, 0)
     for p in range(K):
         err, nflip = gradient_parity(net, em, p, w0, xs[p][0], ys[p][0])
-        say("alexnet worker %d: gradient error %.2e (%d near-ties resolved)" % (p, err, nflip))
+        say("%s worker %d: gradient error %.2e (%d near-ties resolved)" % (model, p, err, nflip))
         assert err < GRAD_TOL
     em.close()
 
 
-def test_alexnet_config2_50_updates(oracle_nn):
+@pytest.mark.parametrize("model,batch,pool", [("alexnet_ds", 128, 16), ("alexnet_3c", 32, 8)])
+def test_alexnet_config2_50_updates(oracle_nn, model, batch, pool):
     K = 4
     d = inputs.durations(2, K, 64)
-    em, net, w0, xs, ys, w_gpu, out = run_both(oracle_nn, "alexnet_ds", 10, 2, K, 3, 12, 0.001, 128, 16, d, total=50)
+    em, net, w0, xs, ys, w_gpu, out = run_both(oracle_nn, model, 10, 2, K, 3, 12, 0.001, batch, pool, d, total=50)
     e, ed = rel_l2(w_gpu, out["w"]), rel_l2(w_gpu - w0, out["w"] - w0)
-    say("alexnet cfg2: weights after 50 updates %.2e, displacement %.2e" % (e, ed))
+    say("%s cfg2: weights after 50 updates %.2e, displacement %.2e" % (model, e, ed))
     assert e < WEIGHT_TOL and ed < 2e-2
     em.close()
 

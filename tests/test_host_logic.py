@@ -101,7 +101,7 @@ def test_clock_and_state_errors_host_only():
 
 
 def test_parameter_layout_matches_documented_one(oracle_nn):
-    for model, ncls, want in [("mlp", 10, 789_258), ("alexnet_ds", 10, 1_387_786), ("resnet110", 100, 1_733_812),
+    for model, ncls, want in [("mlp", 10, 789_258), ("alexnet_ds", 10, 1_387_786), ("alexnet_3c", 10, 1_352_714), ("resnet110", 100, 1_733_812),
                               ("resnet20", 100, None), ("resnet8", 7, None)]:
         mid = B.model_id(model)
         segs = B.dssp_model_segments(mid, ncls)

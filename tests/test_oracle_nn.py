@@ -132,7 +132,7 @@ def test_alexnet_3conv_against_torch_autograd(oracle_nn):
     assert abs(loss - L.item()) < 1e-12
     assert rel(trace["logits"], z.detach().numpy()) < 1e-13
     assert rel(grad, back_to_flat(net, tp)) < 1e-12
-    assert net.n_params() == 4864 + 102464 + 73856 + 6272 * 384 + 384 + 3850
+    assert net.n_params() == 4864 + 102464 + 36928 + 3136 * 384 + 384 + 3850
 
 
 @pytest.mark.parametrize("n", [1, 2])
