@@ -1,12 +1,13 @@
 """Benchmark of the DSSP hot path on one MI355X.
 
-Workload (default): ResNet-110 for CIFAR-shaped synthetic data, batch 128, 8 virtual workers on
-8 HIP streams, DSSP s_L = 3, r_max = 12, lr 0.05, heterogeneous seeded iteration times.
+Workload (default): ResNet-110 for CIFAR-shaped synthetic data, batch 128, 8 virtual workers dealt onto one
+HIP stream per hardware queue (by their push rates, so that every stream carries the same share), DSSP s_L = 3,
+r_max = 12, lr 0.05, heterogeneous seeded iteration times.
 One "step" = one push travelling the whole path: pull -> forward/backward -> push -> apply ->
 decision.  Prints one JSON line: metric, value (pushes/s), ms_per_step, config, roofline (dominant kernel),
 roofline_others, cpu_baseline (the CPU oracle on the first pushes of the same schedule).
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet110|alexnet_ds|mlp|stress]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet110|resnet50|alexnet_ds|alexnet_3c|mlp|stress]
 """
 import argparse
 import json
