@@ -222,7 +222,7 @@ def test_resnet_deep_50_updates(oracle_nn, model, K, batch):
     e_free = rel_l2(w_gpu, out["w"])
     e_self = perturbed_oracle_deviation(net, K, 3, 12, 0.05, w0, d, xs, ys, 50, out["w"])
     say("%s K=%d free-running: weights after 50 updates %.2e; oracle under a 1e-7 perturbation %.2e" % (model, K, e_free, e_self))
-    assert e_free < max(WEIGHT_TOL, 4 * e_self)
+    assert e_free < max(WEIGHT_TOL, min(4 * e_self, 5e-2))
     e, ed = teacher_forced_weights(model, net, K, 3, 12, 0.05, w0, d, xs, ys, batch, 100, 50)
     say("%s K=%d steps from the oracle's snapshots: weights after 50 updates %.2e, displacement %.2e" % (model, K, e, ed))
     assert e < WEIGHT_TOL
@@ -238,14 +238,18 @@ def test_resnet_deep_50_updates(oracle_nn, model, K, batch):
 def test_resnet110_step_gradient_batch128(oracle_nn):
     K = 1
     net = oracle_nn.make_net("resnet110", 100)
-    w0 = inputs.init_weights(segs_of("resnet110", 100), 4, jitter=0.0)
+    w0 = inputs.init_weights(segs_of("resnet110", 100), 4, jitter=0.1)
     xs, ys = inputs.batches(4, K, 1, 128, 100)
     em = Emulation("resnet110", K, 3, 12, 0.05, w0, 128, 100, xs, ys)
     B.dssp_pull(em.ctx, 0, em.w_local[0])
     em.step(0, 0)
     t0 = time.time()
-    err, nflip = gradient_parity(net, em, 0, w0, xs[0][0], ys[0][0])
-    say("resnet110 batch 128: gradient error %.2e (%d near-ties resolved), oracle %.0fs" % (err, nflip, time.time() - t0))
+    stats = {}
+    err, nflip = gradient_parity(net, em, 0, w0, xs[0][0], ys[0][0], stats=stats)
+    say("resnet110 batch 128: gradient error %.2e (%d near-ties resolved, largest margin %.1e, forward error %.1e), oracle %.0fs"
+        % (err, nflip, stats["margin"], stats["forward_err"], time.time() - t0))
+    e = stats["layer_forward_err"]
+    say("forward error by ReLU layer: " + ", ".join("%d: %.1e" % (i, e[i]) for i in sorted(e) if i % 12 == 0 or i == max(e)))
     assert err < GRAD_TOL
     em.close()
 
