@@ -46,8 +46,8 @@ typedef struct dssp_ctx dssp_ctx;
 enum {
     DSSP_OK = 0,
     DSSP_EINVAL = -1,   /* bad argument: null pointer, worker out of range, K < 1, s_L < 0, r_max < 0, ... */
-    DSSP_ESTATE = -2,   /* call not legal now: push / pull by a worker that is waiting for OK or whose
-                           iteration quota of OKs is used up, worker_step before set_model, ... */
+    DSSP_ESTATE = -2,   /* call not legal now: push / pull by a worker that is waiting for OK (the answer to its last
+                           push was "wait" and no later push has released it), worker_step before set_model, ... */
     DSSP_EHIP = -3,     /* a HIP runtime call failed; text in dssp_last_error() */
     DSSP_ENOMEM = -4    /* workspace too small */
 };
@@ -79,7 +79,9 @@ int dssp_create(dssp_ctx** out, float* params_dev, int64_t n_params,
 
 /* Streams: worker in [0, K), or -1 for a stream of the server's own.  hip_stream is a
  * hipStream_t created by the caller (default priority); it must outlive the context.
- * Worker streams the caller did not set are created and owned by the context.  The server
+ * Worker streams the caller did not set - and a worker's stream given as NULL, the legacy default stream, which this
+ * library never enqueues on - are created by the context on first use (non-blocking, default priority) and owned by
+ * it; work the caller has on the default stream is NOT ordered with them: order it with dssp_synchronize or events.  The server
  * has no stream unless one is set: each apply then runs on the pusher's stream, right behind
  * the gradient it consumes, and the context's events keep applies in push order and behind
  * every snapshot still being read.  With a server stream (nullptr takes it away again) the
@@ -152,6 +154,42 @@ int dssp_push(dssp_ctx* ctx, int worker, const float* grad_dev, int64_t t_push_t
 int dssp_push_pull(dssp_ctx* ctx, int worker, const float* grad_dev, int64_t t_push_ticks, float* pull_dst_dev,
                    int* ok_out, int* released_out, int* n_released_out, int* rstar_out, int* grant_out,
                    int* pulled_out, uint64_t* version_out);
+
+/* Alg. 1, server step 2, for pushes that arrive together: "if some other workers send their updates at the same
+ * time, their gradients are aggregated before updating".  m workers push at the same virtual time t_push_ticks.  The
+ * pushes are still counted and decided one at a time, in ascending worker order, exactly as m calls of dssp_push_pull
+ * would (every decision sees the clocks left by the pushes before it); what is aggregated is the device work: ONE
+ * kernel reads the weights once, takes in the m gradients in that order and writes the weights once, and every worker
+ * that may go on after push j - its pusher if answered OK, the workers that push releases - receives the weights as
+ * they are after push j in its snapshot, from the same pass.  Weights, snapshots and stamps are bit-identical to the m
+ * single calls; the traffic is (4 m + 8 + 4 snapshots) bytes per parameter instead of 12 m + 8 snapshots.
+ *   workers           [m] distinct, ascending; m in [1, 16]; none of them waiting for OK
+ *   grads_dev         [m] host array of device pointers, n_params floats each; untouched until that worker's next step
+ *   pull_dst_dev      [K] host array: where worker q's snapshot goes (device, n_params floats, 16-byte aligned), for
+ *                     every worker that can go on (all K to be safe); ignored by a host-only context
+ *   ok_out            [m] answer to each push;  rstar_out, grant_out [m] as in dssp_push (may be NULL)
+ *   n_released_out    [m] how many workers push j released;  released_out [K] their indices, push after push
+ *   pulled_version_out [K] version of the snapshot enqueued for worker q by this call, 0 if none: such a worker goes
+ *                     straight to its next dssp_worker_step (no dssp_pull)
+ * DSSP_EINVAL if more than 32 workers would have to be served by the one kernel (push smaller groups).  On any error
+ * nothing has been counted. */
+int dssp_push_many(dssp_ctx* ctx, int m, const int* workers, const float* const* grads_dev, int64_t t_push_ticks,
+                   float* const* pull_dst_dev, int* ok_out, int* rstar_out, int* grant_out, int* n_released_out,
+                   int* released_out, uint64_t* pulled_version_out);
+
+/* Wall-clock mode: Alg. 2's input is the real time at which a push reaches the server, and Sec. V-C runs on GPUs of
+ * unequal speed.  dssp_worker_step_timed is dssp_worker_step bracketed by reads of the GPU's constant-rate clock on
+ * the worker's stream, followed by a hold that keeps the stream busy until the iteration has lasted
+ * slowdown_permille / 1000 times what it really took (1000: no hold; at most 0.1 s extra): the worker behaves like one
+ * on a GPU that much slower.  dssp_step_done polls, without blocking, whether that iteration (hold included) has left
+ * the stream; if so it reports, in microseconds of device time since the context's first timed step, when the
+ * iteration started, when its gradient was complete and when the hold ended - the last is the timestamp to hand to
+ * dssp_push.  One timed step per worker at a time (DSSP_ESTATE otherwise).  Pinned host memory for the clock values
+ * is allocated on first use. */
+int dssp_worker_step_timed(dssp_ctx* ctx, int worker, const float* x_dev, const int32_t* y_dev,
+                           const float* w_local_dev, float* grad_dev, float* loss_dev, int slowdown_permille);
+int dssp_step_done(dssp_ctx* ctx, int worker, int* done_out, int64_t* t_start_us_out, int64_t* t_gradient_us_out,
+                   int64_t* t_done_us_out);
 
 /* Read-only view of the server's counters (Alg. 1 preamble): t[K] pushes received,
  * r[K] remaining extra-iteration credit, blocked[K] 1 while waiting for OK, version = number

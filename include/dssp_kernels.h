@@ -26,6 +26,18 @@ int dsspk_pull(void* stream, float* dst_dev, const float* w_dev, int64_t n,
  * Results are bit-identical to dsspk_apply followed by dsspk_pull.  dst_stamp_dev may be NULL. */
 int dsspk_apply_pull(void* stream, float* w_dev, const float* g_dev, float* dst_dev, int64_t n, float scale,
                      uint64_t* stamp_dev, uint64_t* dst_stamp_dev, uint64_t version);
+/* Server step 2 for m pushes that arrived at the same time ("aggregated before updating"), in one pass over w:
+ *   w_j = w_{j-1} - scale * g[j-1], j = 1..m (w_0 = w on entry), w = w_m on return, *stamp_dev = version_first + m - 1,
+ * bit-identical to m calls of dsspk_apply in that order.  Snapshot d (d < n_dst) receives w_{dst_after[d]} - the
+ * weights after that many gradients - and *dst_stamp_dev[d] = version_first + dst_after[d] - 1, as dsspk_pull would
+ * have copied between two of the single applies.  g, dst, dst_after, dst_stamp_dev are HOST arrays (of device
+ * pointers / ints); dst_after must be ascending, in [1, m]; the snapshots must be distinct buffers other than w;
+ * dst_stamp_dev or any entry of it may be NULL.  m <= DSSPK_APPLY_MANY_MAX, n_dst <= DSSPK_APPLY_MANY_MAX_DST (-1 beyond). */
+#define DSSPK_APPLY_MANY_MAX 16
+#define DSSPK_APPLY_MANY_MAX_DST 32
+int dsspk_apply_many(void* stream, float* w_dev, int m, const float* const* g_dev, int64_t n, float scale, int n_dst,
+                     float* const* dst_dev, const int* dst_after, uint64_t* const* dst_stamp_dev, uint64_t* stamp_dev,
+                     uint64_t version_first);
 
 /* C[M][N] = op(A)[M][K] * op(B)[K][N] (+ bias[N]) (ReLU if relu).  Element (i,k) of op(A) is
  * A[i*a_rs + k*a_cs], element (k,j) of op(B) is B[k*b_rs + j*b_cs]; C is row-major with
@@ -173,6 +185,20 @@ int dsspk_gap_bwd(void* stream, const float* dy_dev, float* dx_dev, int N, int H
 /* loss = mean_i(logsumexp(z_i) - z_i[y_i]); dz = (softmax(z) - onehot(y)) / m.  loss_dev may be NULL.
  * m <= 1024, C <= 1024. */
 int dsspk_softmax_xent(void* stream, const float* z_dev, const int32_t* y_dev, float* dz_dev, float* loss_dev, int m, int C);
+
+/* Device-side time (the push timestamps of Alg. 2 as real times; a slower worker of Sec. V-C's unequal cluster).
+ * Ticks are those of the GPU's constant-rate wall clock (hipDeviceAttributeWallClockRate, in kHz).
+ * dsspk_clock_stamp: a one-lane kernel stores the current tick to out_a and out_b (either may be NULL, not both).
+ * dsspk_clock_stretch: a one-lane kernel reads *start_dev (a tick stored earlier on the same stream), notes the tick
+ * it starts at (arrival: everything enqueued before it has finished) and holds the stream until
+ * clock - start >= permille / 1000 * (arrival - start), but never longer than max_extra_ticks and never more than about
+ * 0.2 s (a bounded number of sleeps); permille <= 1000 does not wait.  arrival_out / left_out (either may be NULL, not
+ * both) receive the tick of arrival and the tick at which it left.  The out pointers may be device memory or pinned
+ * host memory (stores are system-scope releases). */
+int dsspk_clock_khz(void);      /* ticks per millisecond of the current device's wall clock; -1 on failure */
+int dsspk_clock_stamp(void* stream, uint64_t* out_a, uint64_t* out_b);
+int dsspk_clock_stretch(void* stream, const uint64_t* start_dev, int permille, uint64_t max_extra_ticks,
+                        uint64_t* arrival_out, uint64_t* left_out);
 
 #ifdef __cplusplus
 }

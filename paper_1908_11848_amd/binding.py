@@ -47,6 +47,10 @@ _SIGNATURES = {
     "dssp_push": (c_int, [c_void_p, c_int, c_void_p, c_int64, P(c_int), P(c_int), P(c_int), P(c_int), P(c_int)]),
     "dssp_push_pull": (c_int, [c_void_p, c_int, c_void_p, c_int64, c_void_p, P(c_int), P(c_int), P(c_int), P(c_int), P(c_int),
                                P(c_int), P(ctypes.c_uint64)]),
+    "dssp_push_many": (c_int, [c_void_p, c_int, P(c_int), P(c_void_p), c_int64, P(c_void_p), P(c_int), P(c_int), P(c_int), P(c_int),
+                               P(c_int), P(ctypes.c_uint64)]),
+    "dssp_worker_step_timed": (c_int, [c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int]),
+    "dssp_step_done": (c_int, [c_void_p, c_int, P(c_int), P(c_int64), P(c_int64), P(c_int64)]),
     "dssp_clock": (c_int, [c_void_p, P(c_int64), P(ctypes.c_int32), P(ctypes.c_uint8), P(ctypes.c_uint64)]),
     "dssp_device_stamps": (c_int, [c_void_p, P(ctypes.c_uint64)]),
     "dssp_synchronize": (c_int, [c_void_p]),
@@ -61,6 +65,11 @@ _SIGNATURES = {
     "dsspk_apply": (c_int, [c_void_p, c_void_p, c_void_p, c_int64, c_float, c_void_p, ctypes.c_uint64]),
     "dsspk_pull": (c_int, [c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p]),
     "dsspk_apply_pull": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, ctypes.c_float, c_void_p, c_void_p, ctypes.c_uint64]),
+    "dsspk_apply_many": (c_int, [c_void_p, c_void_p, c_int, P(c_void_p), c_int64, c_float, c_int, P(c_void_p), P(c_int), P(c_void_p),
+                                 c_void_p, ctypes.c_uint64]),
+    "dsspk_clock_khz": (c_int, []),
+    "dsspk_clock_stamp": (c_int, [c_void_p, c_void_p, c_void_p]),
+    "dsspk_clock_stretch": (c_int, [c_void_p, c_void_p, c_int, ctypes.c_uint64, c_void_p, c_void_p]),
     "dsspk_gemm": (c_int, [c_void_p, c_void_p, c_long, c_long, c_void_p, c_long, c_long, c_void_p, c_long,
                            c_int, c_int, c_int, c_void_p, c_int]),
     "dsspk_gemm_splitk_layers": (c_int, [c_int, c_int, c_int]),
@@ -178,6 +187,37 @@ def dssp_push_pull(ctx, worker, grad_dev, t_push_ticks, K, pull_dst_dev):
                                      ctypes.byref(n_rel), ctypes.byref(rstar), ctypes.byref(grant), ctypes.byref(pulled),
                                      ctypes.byref(v)))
     return bool(ok.value), list(rel[:n_rel.value]), rstar.value, grant.value, bool(pulled.value), v.value
+
+
+def dssp_push_many(ctx, workers, grads_dev, t_push_ticks, K, pull_dst_dev):
+    """workers: ascending indices; grads_dev[j]: gradient of workers[j]; pull_dst_dev[q]: snapshot buffer of worker q (all K).
+    -> (ok list, released lists (one per push), r* list, grant list, pulled_version list [K] (0 = no snapshot))"""
+    m = len(workers)
+    wk = (c_int * m)(*workers)
+    g = (c_void_p * m)(*[ptr(x) for x in grads_dev])
+    dst = (c_void_p * K)(*[ptr(x) for x in pull_dst_dev])
+    ok, rstar, grant, n_rel = (c_int * m)(), (c_int * m)(), (c_int * m)(), (c_int * m)()
+    rel = (c_int * K)()
+    pv = (ctypes.c_uint64 * K)()
+    _check(ctx, lib().dssp_push_many(ctx, m, wk, g, int(t_push_ticks), dst, ok, rstar, grant, n_rel, rel, pv))
+    released, at = [], 0
+    for j in range(m):
+        released.append(list(rel[at:at + n_rel[j]]))
+        at += n_rel[j]
+    return [bool(x) for x in ok], released, list(rstar), list(grant), list(pv)
+
+
+def dssp_worker_step_timed(ctx, worker, x_dev, y_dev, w_local_dev, grad_dev, loss_dev=None, slowdown_permille=1000):
+    _check(ctx, lib().dssp_worker_step_timed(ctx, worker, ptr(x_dev), ptr(y_dev), ptr(w_local_dev), ptr(grad_dev), ptr(loss_dev),
+                                             int(slowdown_permille)))
+
+
+def dssp_step_done(ctx, worker):
+    """-> None while the worker's timed step is still on its stream, else (t_start, t_gradient, t_done) in microseconds"""
+    done = c_int()
+    a, b, c = c_int64(), c_int64(), c_int64()
+    _check(ctx, lib().dssp_step_done(ctx, worker, ctypes.byref(done), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return (a.value, b.value, c.value) if done.value else None
 
 
 def dssp_clock(ctx, K):

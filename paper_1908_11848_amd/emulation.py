@@ -105,17 +105,38 @@ class Emulation:
         if self.on_step:
             self.on_step(p, n)
 
-    def run(self, durations, quota=None, total=None, log=True, fused_pull=False):
-        """fused_pull: a worker granted OK by its own push takes its snapshot from the apply kernel (dssp_push_pull)."""
+    def run(self, durations, quota=None, total=None, log=True, fused_pull=False, aggregate=False):
+        """fused_pull: a worker granted OK by its own push takes its snapshot from the apply kernel (dssp_push_pull).
+        aggregate: pushes that share a timestamp are applied by one kernel (dssp_push_many)."""
         out = driver.run_schedule(self.ctx, self.K, durations, quota=quota, total=total,
                                   grad_ptr=lambda p: self.grad[p], pull_dst=lambda p: self.w_local[p],
-                                  step=self.step, log=log, fused_pull=fused_pull)
+                                  step=self.step, log=log, fused_pull=fused_pull, aggregate=aggregate)
         return out
 
-    def schedule(self, durations, quota=None, log=True, fused_pull=False):
+    def schedule(self, durations, quota=None, log=True, fused_pull=False, aggregate=False):
         """Resumable form of run(): returns a driver.Schedule (all workers pulled and started)."""
         return driver.Schedule(self.ctx, self.K, durations, quota=quota, grad_ptr=lambda p: self.grad[p],
-                               pull_dst=lambda p: self.w_local[p], step=self.step, log=log, fused_pull=fused_pull)
+                               pull_dst=lambda p: self.w_local[p], step=self.step, log=log, fused_pull=fused_pull,
+                               aggregate=aggregate)
+
+    def run_wallclock_device(self, total, slowdown=None):
+        """Runs `total` pushes with the controller fed by the DEVICE's clock (driver.run_wallclock_device): every
+        iteration is timed on its stream, and worker p's stream is held until the iteration has lasted slowdown[p]
+        times its real duration (1.0: not at all), which makes the emulated cluster heterogeneous (Sec. V-C).
+        Returns (log, stats)."""
+        permille = [int(round(1000 * f)) for f in (slowdown or [1.0] * self.K)]
+
+        def step_timed(p, n):
+            j = n % len(self.xs[p])
+            if self.before_step:
+                self.before_step(p, n)
+            B.dssp_worker_step_timed(self.ctx, p, self.xs[p][j], self.ys[p][j], self.w_local[p], self.grad[p],
+                                     self.loss[p:p + 1], permille[p])
+            if self.on_step:
+                self.on_step(p, n)
+
+        return driver.run_wallclock_device(self.ctx, self.K, total, grad_ptr=lambda p: self.grad[p],
+                                           pull_dst=lambda p: self.w_local[p], step_timed=step_timed)
 
     def run_wallclock(self, total, min_iteration_us=None):
         """Runs `total` pushes with the controller fed by real completion times (driver.run_wallclock).

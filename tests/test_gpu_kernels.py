@@ -16,9 +16,26 @@ import torch
 pytestmark = pytest.mark.gpu
 
 from paper_1908_11848_amd import binding as B          # noqa: E402
-from gpu_util import dev, empty, host, rel_l2, stream_ptr  # noqa: E402
+from gpu_util import dev, empty, host, max_abs, stream_ptr  # noqa: E402
+import gpu_util                                                # noqa: E402
 
 TOL = 2e-6
+ELEM_TOL = 2e-5         # largest element-wise error, relative to the largest expected magnitude of the tensor
+
+
+def rel_l2(a, b, elem_tol=ELEM_TOL):
+    """Relative L2 error of a against b.  Every comparison in this file is also held element by element: no single
+    element may be off by more than elem_tol of the tensor's largest expected magnitude (a norm can hide one wrong
+    element of a large tensor; this cannot), and none may be NaN."""
+    a, b = np.asarray(a), np.asarray(b)
+    assert a.shape == b.shape or a.size == b.size
+    assert np.isfinite(a).all()
+    e = max_abs(a, b)
+    if os.environ.get("DSSP_TEST_LOG_ELEM"):
+        with open(os.environ["DSSP_TEST_LOG_ELEM"], "a") as f:
+            f.write("%.3e %.3e %s\n" % (e, gpu_util.rel_l2(a, b), os.environ.get("PYTEST_CURRENT_TEST", "")))
+    assert e < elem_tol, ("element-wise error", e)
+    return gpu_util.rel_l2(a, b)
 
 
 def rc(x):
@@ -63,6 +80,80 @@ def test_apply_and_pull_in_one_pass(n):
     assert np.array_equal(host(W1), host(W2)) and np.array_equal(host(d1), host(d2)) and np.array_equal(host(d2), host(W2))
     assert host(st1).tolist() == host(st2).tolist() == [5, 5]
     assert rel_l2(host(W2), w0.astype(np.float64) - np.float32(0.37).astype(np.float64) * gr.astype(np.float64)) < 1e-6
+
+
+@pytest.mark.parametrize("n,m,after", [(1, 1, [1]), (3, 2, [1, 2]), (1027, 3, [1, 1, 3]), (100003, 5, [2, 5, 5]), ((1 << 20) + 1, 16, list(range(1, 17))),
+                                       (4096, 7, []), (262147, 4, [4])])
+def test_aggregated_apply_equals_single_applies_and_pulls(n, m, after):
+    """m simultaneous pushes in one pass over the weights (Alg. 1, server step 2, "aggregated"): the weights and every
+    snapshot taken between two of the pushes carry the bits m single applies and pulls would have left."""
+    g = np.random.default_rng(n + m)
+    w0 = f32(g, n)
+    grads = [f32(g, n, 1e-2) for _ in range(m)]
+    L = B.lib()
+    s = stream_ptr()
+    scale = 0.05 / 8
+    # one by one
+    W1 = dev(w0)
+    G = [dev(x) for x in grads]
+    st1 = torch.zeros(1 + len(after), dtype=torch.int64, device="cuda")
+    snaps1 = [empty(n) for _ in after]
+    for j in range(m):
+        rc(L.dsspk_apply(s, W1.data_ptr(), G[j].data_ptr(), n, scale, st1.data_ptr(), 100 + j))
+        for d, a in enumerate(after):
+            if a == j + 1:
+                rc(L.dsspk_pull(s, snaps1[d].data_ptr(), W1.data_ptr(), n, st1[1 + d:].data_ptr(), st1.data_ptr()))
+    # together
+    import ctypes
+    W2 = dev(w0)
+    st2 = torch.zeros(1 + len(after), dtype=torch.int64, device="cuda")
+    snaps2 = [empty(n) for _ in after]
+    gp = (ctypes.c_void_p * m)(*[x.data_ptr() for x in G])
+    nd = len(after)
+    dp = (ctypes.c_void_p * max(nd, 1))(*[x.data_ptr() for x in snaps2])
+    da = (ctypes.c_int * max(nd, 1))(*after)
+    ds = (ctypes.c_void_p * max(nd, 1))(*[st2[1 + d:].data_ptr() for d in range(nd)])
+    rc(L.dsspk_apply_many(s, W2.data_ptr(), m, gp, n, scale, nd, dp, da, ds, st2.data_ptr(), 100))
+    assert np.array_equal(host(W1), host(W2))
+    for a, b in zip(snaps1, snaps2):
+        assert np.array_equal(host(a), host(b))
+    assert host(st1).tolist() == host(st2).tolist()
+    want = w0.astype(np.float64) - np.float64(np.float32(scale)) * np.sum([x.astype(np.float64) for x in grads], axis=0)
+    assert rel_l2(host(W2), want) < 1e-6 and max_abs(host(W2), want) < 1e-6
+    # rejected on the host: too many pushes, a snapshot index out of order, a snapshot that is the weight vector
+    assert L.dsspk_apply_many(s, W2.data_ptr(), 17, gp, n, scale, 0, None, None, None, st2.data_ptr(), 1) == -1
+    if nd >= 2 and after[0] != after[-1]:
+        bad = (ctypes.c_int * nd)(*reversed(after))
+        assert L.dsspk_apply_many(s, W2.data_ptr(), m, gp, n, scale, nd, dp, bad, ds, st2.data_ptr(), 1) == -1
+    if nd:
+        dp_bad = (ctypes.c_void_p * nd)(*([W2.data_ptr()] + [x.data_ptr() for x in snaps2[1:]]))
+        assert L.dsspk_apply_many(s, W2.data_ptr(), m, gp, n, scale, nd, dp_bad, da, ds, st2.data_ptr(), 1) == -1
+
+
+def test_device_clock_stamp_and_bounded_hold():
+    """The clock kernels of the wall-clock mode: stamps on one stream increase, and a hold keeps the stream until the
+    iteration has lasted the given multiple of its real duration (capped, so it always ends)."""
+    L = B.lib()
+    s = stream_ptr()
+    khz = L.dsspk_clock_khz()
+    assert khz >= 1000
+    t = torch.zeros(8, dtype=torch.int64, device="cuda")
+    x = torch.randn(1 << 24, device="cuda")
+    y = (x * 2 + 1) * 1.0001                                                 # (first use loads these kernels)
+    torch.cuda.synchronize()
+    rc(L.dsspk_clock_stamp(s, t.data_ptr(), None))
+    y = x * 2 + 1                                                            # some real work on the stream: about a millisecond
+    for _ in range(20):
+        y = y * 1.0001
+    rc(L.dsspk_clock_stretch(s, t.data_ptr(), 3000, 100 * khz, t[1:].data_ptr(), t[2:].data_ptr()))
+    rc(L.dsspk_clock_stamp(s, t[3:].data_ptr(), t[4:].data_ptr()))
+    rc(L.dsspk_clock_stretch(s, t.data_ptr(), 100000, khz // 2, t[5:].data_ptr(), t[6:].data_ptr()))   # 100x, capped at 0.5 ms
+    start, arrival, left, after_a, after_b, arr2, left2, _ = host(t).tolist()
+    assert start < arrival <= left <= after_a == after_b <= arr2 <= left2
+    spent = arrival - start
+    assert spent > 0 and left - start >= 3 * spent - 2 and left - start < 3 * spent + khz // 2      # 3x, within 0.5 ms
+    assert khz // 2 <= left2 - arr2 < khz // 2 + khz // 2                                           # the cap, not 100x
+    assert L.dsspk_clock_stamp(s, None, None) == -1 and L.dsspk_clock_stretch(s, None, 2000, 1, t.data_ptr(), None) == -1
 
 
 # ------------------------------------------------------------------ GEMM (fully connected layers)

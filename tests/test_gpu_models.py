@@ -315,7 +315,129 @@ def test_server_stress_config5(oracle_nn):
     em.close()
 
 
+# ------------------------------------------------------------------ simultaneous pushes aggregated
+def tie_durations(kind, K, n):
+    if kind == "rounded":            # the homogeneous cluster's +-5 % jitter on a grid of 0.05: pushes coincide
+        return np.maximum(np.rint(inputs.durations(2, K, n) / 50_000).astype(np.int64) * 50_000, 50_000)
+    return np.full((K, n), 1_000_000, dtype=np.int64)        # identical workers: a whole round arrives together
+
+
+def test_aggregated_pushes_stress_vector(oracle_nn):
+    """Alg. 1, server step 2, "aggregated": pushes with one timestamp applied by one kernel (dssp_push_many).  25 M
+    parameters, 16 workers, tables with exact ties: log bit-exact against the oracle (which takes the pushes one by
+    one), weights and snapshots bit-identical to this library's own one-by-one path, weights within 1e-6 of the oracle."""
+    K, n, lr = 16, 25_000_000, 0.01
+    w0 = inputs.stress_weights(n)
+    g = inputs.stress_grads(K, n)
+    for kind, s_L, r_max, total in (("rounded", 3, 15, 50), ("equal", 0, 0, 48), ("equal", 3, 15, 50)):
+        d = tie_durations(kind, K, 64)
+        out = ps.run(K, s_L, r_max, lr, w0, d, lambda p, i, w: (0.0, g[p]), total=total)
+        em = Emulation("none", K, s_L, r_max, lr, w0, grads=g)
+        log, st = em.run(d, total=total, aggregate=True)
+        assert log == out["log"] and st["aggregated"] >= total // 2
+        w_many = em.weights()
+        stamps = B.dssp_device_stamps(em.ctx, K)
+        snaps = [em.w_local[p].cpu().numpy() for p in range(K)]
+        em.close()
+        em = Emulation("none", K, s_L, r_max, lr, w0, grads=g)
+        log1, _ = em.run(d, total=total)
+        assert log1 == log and np.array_equal(em.weights(), w_many) and B.dssp_device_stamps(em.ctx, K) == stamps
+        for p in range(K):
+            assert np.array_equal(em.w_local[p].cpu().numpy(), snaps[p]), (kind, p)
+        em.close()
+        e = rel_l2(w_many, out["w"])
+        say("aggregated %s (%d,%d): %d of %d pushes in groups, weights vs oracle %.2e" % (kind, s_L, r_max, st["aggregated"], total, e))
+        assert e < 1e-6 and np.max(np.abs(w_many - out["w"])) < 1e-5
+        pulls = {}
+        for kind_, p, T, tp, rp, v, a0, a1 in log:
+            if kind_ == R.PULL:
+                pulls[p] = a0
+        assert stamps[0] == total and stamps[1:] == [pulls[p] for p in range(K)]
+
+
+@pytest.mark.parametrize("model,K,batch,ncls,kind,s_L,r_max", [("resnet8", 4, 16, 100, "rounded", 3, 12), ("alexnet_ds", 4, 32, 10, "equal", 0, 0),
+                                                            ("mlp", 4, 32, 10, "equal", 1, 2)])
+def test_aggregated_pushes_model(oracle_nn, model, K, batch, ncls, kind, s_L, r_max):
+    """The same on a model: 50 updates with simultaneous pushes aggregated; log bit-exact, weights bit-identical to the
+    one-by-one path (also with the server's applies on a stream of their own) and within 1e-3 of the oracle."""
+    lr = {"resnet8": 0.05, "alexnet_ds": 0.001, "mlp": 0.01}[model]
+    d = tie_durations(kind, K, 64)
+    net = oracle_nn.make_net(model, ncls)
+    w0 = inputs.init_weights(segs_of(model, ncls), 4, jitter=0.1)
+    xs, ys = inputs.batches(4, K, 4, batch, ncls, flat=(model == "mlp"))
+    out = ps.run(K, s_L, r_max, lr, w0, d, ps.model_grad_fn(net, xs, ys), total=50)
+    results = []
+    for aggregate, server_stream in ((True, False), (False, False), (True, True)):
+        em = Emulation(model, K, s_L, r_max, lr, w0, batch, ncls, xs, ys, server_stream=server_stream)
+        log, st = em.run(d, total=50, aggregate=aggregate)
+        assert log == out["log"]
+        assert (st["aggregated"] >= 20) == aggregate
+        results.append((em.weights(), B.dssp_device_stamps(em.ctx, K)))
+        em.close()
+    assert all(np.array_equal(results[0][0], w) and results[0][1] == st for w, st in results[1:])
+    e = rel_l2(results[0][0], out["w"])
+    say("%s with aggregated pushes (%s ties): weights after 50 updates %.2e" % (model, kind, e))
+    assert e < WEIGHT_TOL
+
+
 # ------------------------------------------------------------------ controller fed by real push times
+def replay_wallclock_log(log, K, total):
+    """Iteration times as they happened (push time minus the time of the pull that started the iteration), for the oracle."""
+    d = np.full((K, total + 2), 10**12, dtype=np.int64)
+    started, n_it, blocks = {}, [0] * K, 0
+    for kind, p, T, tp, rp, v, a0, a1 in log:
+        if kind == R.PULL:
+            started[p] = T
+        elif kind == R.PUSH:
+            d[p][n_it[p]] = T - started[p]
+            assert d[p][n_it[p]] >= 1
+            n_it[p] += 1
+        elif kind == R.BLOCK:
+            blocks += 1
+    return d, n_it, blocks
+
+
+def test_device_clock_driven_schedule_on_an_unequal_cluster(oracle_nn):
+    """Alg. 2's input as the paper has it: the real time of each push, here the device clock at the moment the worker's
+    stream is done with the iteration; the cluster of Sec. V-C emulated by holding worker p's stream until its iteration
+    has lasted (1, 1, 2, 3.5) times its real duration.  The schedule differs from run to run; whatever it was, the
+    oracle fed with the iteration times read back from the log must take the same decisions (bit-exact log) and arrive
+    at the same weights, and the device's stamps must agree with the log."""
+    K, s_L, r_max, lr, batch, total, model = 4, 3, 12, 0.001, 128, 120, "alexnet_ds"
+    slow = [1.0, 1.0, 2.0, 3.5]
+    net = oracle_nn.make_net(model, 10)
+    w0 = inputs.init_weights(segs_of(model, 10), 3, jitter=0.1)
+    xs, ys = inputs.batches(3, K, 4, batch, 10)
+    em = Emulation(model, K, s_L, r_max, lr, w0, batch, 10, xs, ys)
+    log, st = em.run_wallclock_device(total, slowdown=slow)
+    w_gpu = em.weights()
+    stamps = B.dssp_device_stamps(em.ctx, K)
+    em.close()
+    assert st["pushes"] == total
+    d, n_it, blocks = replay_wallclock_log(log, K, total)
+    # the hold really stretched the iterations: done - start >= slowdown * (gradient finished - start)
+    ratio = []
+    for p in range(K):
+        for t_start, t_grad, t_done in st["times"][p]:
+            assert t_start <= t_grad <= t_done
+            assert t_done - t_start >= slow[p] * (t_grad - t_start) - 5         # times are truncated to whole microseconds
+        it = np.array([t[2] - t[0] for t in st["times"][p][2:]], dtype=np.float64)
+        ratio.append(float(np.median(it)))
+    say("device-clock schedule: pushes per worker %s, %d blocks, last push at %d us, median iteration %s us" % (n_it, blocks, st["T_end"], [int(r) for r in ratio]))
+    # the emulated GPUs are as unequal as asked (how often a worker pushes is the controller's business: the run above
+    # may well grant the middle worker more extra iterations than the fastest ones)
+    assert ratio[3] > 1.3 * ratio[2] > 1.3 * 1.3 * max(ratio[0], ratio[1]) and min(n_it[0], n_it[1]) >= n_it[3] and blocks > 0
+    out = ps.run(K, s_L, r_max, lr, w0, d, ps.model_grad_fn(net, xs, ys), total=total)
+    assert log == out["log"]
+    e = rel_l2(w_gpu, out["w"])
+    say("device-clock schedule: weights after %d updates vs the oracle on the replayed schedule %.2e" % (total, e))
+    assert e < WEIGHT_TOL
+    pulls = {}
+    for kind, p, T, tp, rp, v, a0, a1 in log:
+        if kind == R.PULL:
+            pulls[p] = a0
+    assert stamps[0] == total and stamps[1:] == [pulls[p] for p in range(K)]
+
 def test_wallclock_driven_schedule_replays_through_the_oracle(oracle_nn):
     """Pushes happen when the device has really finished a gradient (heterogeneous workers: a floor on the duration of
     their iterations), so the schedule differs from run to run.  Whatever it was, the oracle fed with the iteration times

@@ -34,12 +34,76 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert names == set(B._SIGNATURES), names ^ set(B._SIGNATURES)      # binding and headers list the same calls
 
 
-def host_log(K, s_L, r_max, d, quota=None, total=None, fused_pull=False):
+def host_log(K, s_L, r_max, d, quota=None, total=None, fused_pull=False, aggregate=False, stats=None):
     ctx = B.dssp_create(None, 0, K, s_L, r_max, 0.1)
     try:
-        return driver.run_schedule(ctx, K, d, quota=quota, total=total, fused_pull=fused_pull)[0]
+        log, st = driver.run_schedule(ctx, K, d, quota=quota, total=total, fused_pull=fused_pull, aggregate=aggregate)
+        if stats is not None:
+            stats.update(st)
+        return log
     finally:
         B.dssp_destroy(ctx)
+
+
+def tie_table(kind, K, n, seed=0):
+    """Iteration-time tables in which pushes of different workers coincide."""
+    if kind == "rounded":            # the homogeneous cluster's +-5 % jitter on a grid of 0.05
+        return np.maximum(np.rint(inputs.durations(2, K, n) / 50_000).astype(np.int64) * 50_000, 50_000)
+    if kind == "equal":              # identical workers: every push of a round arrives together
+        return np.full((K, n), 1_000_000, dtype=np.int64)
+    g = np.random.default_rng(seed)  # small integers: ties of every size, stragglers included
+    return g.integers(1, 5, (K, n)).astype(np.int64) * np.where(g.random((K, 1)) < 0.3, 3, 1)
+
+
+@pytest.mark.parametrize("kind,K,s_L,r_max", [("rounded", 4, 3, 12), ("equal", 8, 0, 0), ("equal", 16, 3, 15), ("equal", 5, 1, 0),
+                                              ("small", 8, 3, 12), ("small", 16, 0, 0), ("small", 3, 2, 4), ("small", 20, 1, 2)])
+def test_same_timestamp_pushes_aggregated_take_the_oracles_decisions(kind, K, s_L, r_max):
+    """Alg. 1 server step 2: simultaneous pushes are aggregated.  Handing them to the server together (dssp_push_many)
+    must leave every decision, clock, version and pull as the oracle's one-by-one processing has them."""
+    for seed in range(3):
+        d = tie_table(kind, K, 80, seed)
+        for total, quota in ((None, 60), (157, None)):
+            olog, st, _ = R.simulate(K, s_L, r_max, d, quota=quota, total=total)
+            stats = {}
+            assert host_log(K, s_L, r_max, d, quota=quota, total=total, aggregate=True, stats=stats) == olog
+            assert stats["aggregated"] > 0 and stats["pushes"] == st.version
+            assert host_log(K, s_L, r_max, d, quota=quota, total=total, fused_pull=True, aggregate=True) == olog
+
+
+def test_controller_search_equals_the_double_loop_of_alg2():
+    """The library finds the closest pair of extrapolated push times by one division per candidate; the oracle scans all
+    pairs as Alg. 2 prints it.  Same r* on random tables: long and short intervals, exact ties, zero and negative
+    intervals (timestamps are the caller's), r_max up to 300."""
+    rnd = random.Random(5)
+    for case in range(300):
+        r_max = rnd.choice([0, 1, 2, 5, 12, 15, 40, 300])
+        scale = rnd.choice([1, 10, 1000, 10**9, 10**15])
+        a1, b1 = rnd.randrange(0, 50) * scale, rnd.randrange(0, 50) * scale
+        ip, isl = rnd.randrange(-3, 40) * scale // rnd.choice([1, 1, 7]), rnd.randrange(-3, 40) * scale // rnd.choice([1, 1, 3])
+        # worker 0 = p pushes twice (at a1 - ip... then a1), worker 1 = the slowest pushes at b1 - isl, then b1, in a
+        # 2-worker context with s_L = 0 where worker 0 is made the fastest by one more push
+        ctx = B.dssp_create(None, 0, 2, 0, r_max, 0.1)
+        seq = [(1, b1 - isl), (0, a1 - 2 * ip)]
+        st = R.ServerState(2, 0, r_max)
+        ok_all = True
+        for p, T in seq + [(1, b1), (0, a1 - ip), (0, a1)]:
+            if st.blocked[p]:
+                ok_all = False
+                break
+            want = R.server_on_push(st, p, T)
+            ok, rel, rstar, grant = B.dssp_push(ctx, p, None, T, 2)
+            assert (ok, rstar, grant, rel) == want, (case, p, T, want, (ok, rstar, grant, rel))
+        B.dssp_destroy(ctx)
+    # and directly against the definition on the controller's own inputs
+    for case in range(200):
+        r_max = rnd.choice([0, 3, 12, 100])
+        A = [[rnd.randrange(-10**6, 10**6), rnd.randrange(-10**6, 10**6)] for _ in range(2)]
+        t = [5, 2]
+        want = R.synchronization_controller(A, t, 0, r_max)
+        sim_p = [A[0][0] + i * (A[0][0] - A[0][1]) for i in range(r_max + 1)]
+        sim_s = [A[1][0] + (k + 1) * (A[1][0] - A[1][1]) for k in range(r_max + 1)]
+        best = min(abs(a - b) for a in sim_p for b in sim_s)
+        assert want == min(i for i, a in enumerate(sim_p) if min(abs(a - b) for b in sim_s) == best)
 
 
 @pytest.mark.parametrize("seed", range(20))
