@@ -57,6 +57,20 @@ int dsspk_gemm_splitk(void* stream, const float* A_dev, long a_rs, long a_cs, co
 int dsspk_colsum(void* stream, const float* X_dev, float* out_dev, float* scratch_dev, long M, int N);
 /* Floats of scratch_dev dsspk_colsum needs for an [M][N] matrix (0 for short matrices: scratch_dev may be NULL). */
 size_t dsspk_colsum_scratch_floats(long M, int N);
+/* dsspk_colsum for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The slab sums go to a fixed buffer that is part of the
+ * library image on every GPU (DSSPK_COLSUM_NOALLOC_MAX_N * 256 floats = 4 MiB, held until the process ends); the call
+ * allocates and frees nothing and gives the same bits as dsspk_colsum.  X_dev and out_dev are the caller's, as above.
+ * Returns 0, -1 (null pointer, M < 1 or N < 1), DSSPK_NOALLOC_ETOOBIG (N > DSSPK_COLSUM_NOALLOC_MAX_N: the matrix has
+ * more columns than the fixed buffer holds slab sums for; use dsspk_colsum with a workspace) or DSSPK_NOALLOC_EHIP (the
+ * buffer's address could not be resolved on the current device), else the HIP error code of the launch.
+ * All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (different streams) race; calls on
+ * one stream, or otherwise ordered, are safe.  Nothing needs clearing between calls (every slab sum read was written
+ * by the same call). */
+#define DSSPK_COLSUM_NOALLOC_MAX_N 4096
+#define DSSPK_NOALLOC_ETOOBIG (-2)
+#define DSSPK_NOALLOC_EHIP (-3)
+int dsspk_colsum_noalloc(void* stream, const float* X_dev, float* out_dev, long M, int N);
 
 /* Convolution (cross-correlation, zero padding), implicit GEMM on fp32 MFMA.
  * Ho = (H + 2*pad - KH)/stride + 1.  bias_dev may be NULL; relu applies max(.,0) to the output.

@@ -77,6 +77,7 @@ _SIGNATURES = {
                                   c_int, c_int, c_int, c_void_p, c_int, c_void_p, c_int]),
     "dsspk_colsum": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_long, c_int]),
     "dsspk_colsum_scratch_floats": (c_size_t, [c_long, c_int]),
+    "dsspk_colsum_noalloc": (c_int, [c_void_p, c_void_p, c_void_p, c_long, c_int]),
     "dsspk_conv_fwd": (c_int, [c_void_p] * 5 + [c_int] * 10 + [c_void_p]),
     "dsspk_conv_fwd_stat_parts": (c_int, [c_int] * 9),
     "dsspk_conv_fwd_prebn": (c_int, [c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_float, c_void_p, c_void_p,

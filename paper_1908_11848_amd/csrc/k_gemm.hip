@@ -2,6 +2,8 @@
 // One workgroup (4 wavefronts) owns a 64 x 64 tile of C; wavefront w owns the 32 x 32
 // quadrant (w / 2, w % 2).  Operands come in through generic strides, so the same kernel
 // serves y = x W (+b), dx = dy W^T and dW = x^T dy of Alg. 1's worker gradient.
+#include <mutex>
+
 #include "mma.hpp"
 #include "../../include/dssp_kernels.h"
 
@@ -185,4 +187,44 @@ extern "C" int dsspk_colsum(void* stream, const float* X, float* out, float* scr
     hipLaunchKernelGGL(colsum_kernel, dim3(ceil_div(N, 64), slabs), dim3(256), 0, s, X, scratch, M, N, rps);
     hipLaunchKernelGGL(colsum_kernel, dim3(ceil_div(N, 64), 1), dim3(256), 0, s, scratch, out, (long)slabs, N, (long)slabs);
     return DSSPK_LAUNCH_RC();
+}
+
+// ---- dsspk_colsum for callers that may not allocate: the slab sums go to device memory that is part of the library image
+namespace {
+
+constexpr int NOALLOC_MAX_N = DSSPK_COLSUM_NOALLOC_MAX_N;
+constexpr int MAX_DEVICES = 64;
+
+// One copy per GPU the library is loaded on, kept until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress: the device address it resolves to (per device) is what kernels and copies are given.
+static __device__ __align__(256) float colsum_scratch[(size_t)COLSUM_SLABS * NOALLOC_MAX_N];
+
+std::mutex scratch_mutex;
+float* scratch_ptr[MAX_DEVICES];        // device address of colsum_scratch on each device, resolved on first use there
+
+int resolve_scratch(float** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return DSSPK_NOALLOC_EHIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(colsum_scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return DSSPK_NOALLOC_EHIP;
+        }
+        scratch_ptr[dev] = static_cast<float*>(ptr);
+    }
+    *out = scratch_ptr[dev];
+    return 0;
+}
+
+}  // namespace
+
+extern "C" int dsspk_colsum_noalloc(void* stream, const float* X, float* out, long M, int N) {
+    if (!X || !out || M < 1 || N < 1) return -1;
+    if (N > NOALLOC_MAX_N) return DSSPK_NOALLOC_ETOOBIG;
+    float* scratch = nullptr;
+    if (int rc = resolve_scratch(&scratch)) return rc;
+    // every slab row the second pass reads is written by the first pass of the same call, so nothing has to be cleared
+    return dsspk_colsum(stream, X, out, scratch, M, N);
 }
