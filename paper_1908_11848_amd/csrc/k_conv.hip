@@ -217,6 +217,8 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
 // every slice, the four wavefronts' tiles are summed in a fixed order at the end.
 //   VEC  : Cin is a multiple of 16, rows of the tile are the channels of tap blockIdx.y.
 //   !VEC : rows are the flattened (tap, ci) index (first layer, Cin = 3), blockIdx.y = 0.
+// Layers wider than one tile (more than 16 * CI_T input or 16 * CO_T output channels) are cut into channel slices,
+// one per blockIdx.z: slice z covers input channels [ci0, ci0 + CIP) (VEC only) and output channels [co0, co0 + COP).
 template <int CI_T, int CO_T, bool VEC>
 __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy,
                                                              float* __restrict__ partial, ConvGeom g, int stages, int rows_total) {
@@ -230,6 +232,8 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
     const int tap = blockIdx.y;
     const int kh = tap / g.KW, kw = tap - kh * g.KW;
     const long p_begin = (long)blockIdx.x * stages * PIX;
+    const int ci_slices = VEC ? g.IC / CIP : 1;
+    const int ci0 = ((int)blockIdx.z % ci_slices) * CIP, co0 = ((int)blockIdx.z / ci_slices) * COP;
 
     floatx4 acc[CI_T][CO_T];
     mma::zero(acc);
@@ -247,7 +251,7 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
                     const int ow = (int)(m % g.OW), oh = (int)((m / g.OW) % g.OH), n = (int)(m / ((long)g.OW * g.OH));
                     int sh, sw;
                     if (src_pixel<false>(g, oh, ow, kh, kw, sh, sw))
-                        v = *reinterpret_cast<const float4*>(x + (((long)n * g.SH + sh) * g.SW + sw) * g.IC + 4 * c4);
+                        v = *reinterpret_cast<const float4*>(x + (((long)n * g.SH + sh) * g.SW + sw) * g.IC + ci0 + 4 * c4);
                 }
                 *reinterpret_cast<float4*>(&Xs[pix * LDA + 4 * c4]) = v;
             }
@@ -270,7 +274,7 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
         for (int idx = tid; idx < PIX * (COP / 4); idx += THREADS) {
             const int pix = idx / (COP / 4), c4 = idx % (COP / 4);
             const long m = p0 + pix;
-            const float4 v = m < g.M ? *reinterpret_cast<const float4*>(dy + m * g.OC + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            const float4 v = m < g.M ? *reinterpret_cast<const float4*>(dy + m * g.OC + co0 + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
             *reinterpret_cast<float4*>(&Ds[pix * LDB + 4 * c4]) = v;
         }
         __syncthreads();
@@ -296,11 +300,11 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
     }
     __syncthreads();
     // partial[chunk][row][co]; VEC: row = tap*Cin + ci, else row = flattened (tap, ci)
-    const int rows = VEC ? g.IC : rows_total;
-    float* out = partial + ((long)blockIdx.x * rows_total + (VEC ? (long)tap * g.IC : 0)) * g.OC;
-    for (int idx = tid; idx < rows * g.OC; idx += THREADS) {
-        const int rr = idx / g.OC, co = idx - rr * g.OC;
-        out[idx] = Red[rr * COP + co];
+    const int rows = VEC ? CIP : rows_total;
+    float* out = partial + ((long)blockIdx.x * rows_total + (VEC ? (long)tap * g.IC + ci0 : 0)) * g.OC + co0;
+    for (int idx = tid; idx < rows * COP; idx += THREADS) {
+        const int rr = idx / COP, co = idx - rr * COP;
+        out[(long)rr * g.OC + co] = Red[rr * COP + co];
     }
 }
 
@@ -456,9 +460,9 @@ int wgrad_stages(const ConvGeom& g, int grid_y) {
 
 template <bool DGRAD, bool VEC>
 int launch_igemm(hipStream_t s, const float* src, const float* w, const float* bias, const float* add, float* dst, const ConvGeom& g, int relu) {
-    const int bn = g.OC >= 64 ? 64 : g.OC;
-    if (bn != 16 && bn != 32 && bn != 64) return -1;
-    if (g.OC % bn) return -1;
+    // output-channel tile: the widest of 64, 32, 16 that divides the layer
+    const int bn = g.OC % 64 == 0 ? 64 : g.OC % 32 == 0 ? 32 : g.OC % 16 == 0 ? 16 : 0;
+    if (!bn) return -1;
     // small problems take 64-pixel tiles so that the grid still covers the chip
     const bool small = g.M < 128L * 512;
     dim3 grid(ceil_div(g.M, small ? 64 : 128), g.OC / bn);
@@ -540,7 +544,7 @@ extern "C" size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, 
 // tj.blocks > 0 asks the kernel to carry the batch-norm sums job (only the specialised 3x3 and the tile kernels can).
 static int wgrad_stage1(hipStream_t s, const float* x, const float* dy, float* scratch, const ConvGeom& g, int N, int H, int W,
                         int Cin, int Cout, int KH, int KW, int stride, int pad, const jobs::TotalsJob& tj, int* chunks_out) {
-    if (Cout != 16 && Cout != 32 && Cout != 64) return -1;
+    if (Cout < 16 || Cout % 16) return -1;
     const bool vec = Cin % 16 == 0;
     const int rows_total = KH * KW * Cin;
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
@@ -555,9 +559,17 @@ static int wgrad_stage1(hipStream_t s, const float* x, const float* dy, float* s
     const int chunks = ceil_div(g.M, 64L * stages);
     *chunks_out = chunks;
     dim3 grid(chunks, gy);
+    // channel slices of the widest tile that divides the layer: 64, 32 or 16 channels
+    const int cop = Cout % 64 == 0 ? 64 : Cout % 32 == 0 ? 32 : 16;
+    const int cip = !vec ? 0 : Cin % 64 == 0 ? 64 : Cin % 32 == 0 ? 32 : 16;
+    const bool sliced = Cout > 64 || (vec && Cin > 64);
 #define GO(CI, CO, V) hipLaunchKernelGGL((conv_wgrad_kernel<CI, CO, V>), grid, dim3(THREADS), 0, s, x, dy, scratch, g, stages, rows_total)
-#define GO_CO(CI, V) do { if (Cout == 16) GO(CI, 1, V); else if (Cout == 32) GO(CI, 2, V); else GO(CI, 4, V); } while (0)
-    if (vec && (Cin / 16) * (Cout / 16) >= 4 && Cout >= 32 && (Cin == 16 || Cin == 32 || Cin == 64)) {
+#define GO_CO(CI, V) do { if (cop == 16) GO(CI, 1, V); else if (cop == 32) GO(CI, 2, V); else GO(CI, 4, V); } while (0)
+    if (sliced) {
+        if (tj.blocks) return -1;
+        grid.z = (unsigned)((Cout / cop) * (vec ? Cin / cip : 1));
+    }
+    if (!sliced && vec && (Cin / 16) * (Cout / 16) >= 4 && Cout >= 32 && (Cin == 16 || Cin == 32 || Cin == 64)) {
         if (Cin == 64 && Cout == 64) return launch_wgrad_tile<4, 4>(s, x, dy, scratch, g, stages, grid, tj);
         if (Cin == 32 && Cout == 64) return launch_wgrad_tile<2, 4>(s, x, dy, scratch, g, stages, grid, tj);
         if (Cin == 32 && Cout == 32) return launch_wgrad_tile<2, 2>(s, x, dy, scratch, g, stages, grid, tj);
@@ -566,7 +578,7 @@ static int wgrad_stage1(hipStream_t s, const float* x, const float* dy, float* s
     }
     if (tj.blocks) return -1;
     if (vec) {
-        if (Cin == 16) GO_CO(1, true); else if (Cin == 32) GO_CO(2, true); else if (Cin == 64) GO_CO(4, true); else return -1;
+        if (cip == 16) GO_CO(1, true); else if (cip == 32) GO_CO(2, true); else GO_CO(4, true);
     } else {
         const int tiles = ceil_div(rows_total, 16);
         if (tiles <= 2) GO_CO(2, false); else if (tiles <= 5) GO_CO(5, false); else return -1;

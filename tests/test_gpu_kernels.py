@@ -224,6 +224,10 @@ CONV_CASES = [  # N, H, Cin, Cout, k, stride, pad, bias+relu
     (2, 32, 3, 64, 5, 1, 2, True),
     (3, 15, 64, 64, 5, 1, 2, True),
     (1, 7, 16, 16, 3, 1, 1, False),          # fewer pixels than one tile
+    (2, 8, 64, 128, 3, 1, 1, True),          # wider than one channel tile: the d-filter kernel works in channel slices
+    (3, 9, 96, 80, 3, 2, 1, False),
+    (2, 7, 128, 192, 5, 1, 2, True),
+    (2, 12, 3, 96, 5, 1, 2, True),
     (128, 32, 16, 16, 3, 1, 1, False),       # benchmark shapes, batch 128
     (128, 16, 32, 32, 3, 1, 1, False),
     (128, 8, 64, 64, 3, 1, 1, False),
