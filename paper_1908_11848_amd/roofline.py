@@ -26,6 +26,8 @@ W = (4/9) * 2 * N * H * H * C * 9 * C FLOP, the matrix-core work of one 3x3 conv
                    BN sums job
     bn_fwd / bn_bwd  stand-alone batch-norm kernels (irregular layers only)      4 T / 7 T
     apply / pull   server update and snapshot copy                               12 / 8 bytes per parameter
+    apply_pull     update + the pusher's snapshot in one pass                    16 bytes per parameter
+    apply_many4    four simultaneous pushes + one snapshot in one pass           28 bytes per parameter (56 one by one)
 A case is bound by whichever of its two floors is higher: its FLOP at 157.3 TFLOP/s (fp32 matrix cores: 256 CUs
 x 4 SIMDs x 64 FLOP/cycle x 2.4 GHz) or its bytes at 8 TB/s (HBM); with minimal filtering that is HBM for every
 3x3 case.  HBM traffic per launch (`traffic`)
@@ -61,6 +63,7 @@ def case_list(n_params=N_PARAMS):
     out += [("bn_fwd_32x32x16", 2, 0), ("bn_bwd_32x32x16", 2, 2)]
     for n in sorted({n_params, 25_000_000}):
         out += [("apply_%d" % n, 1, 0), ("pull_%d" % n, 1, 0)]
+    out += [("apply_pull_25000000", 1, 0), ("apply_many4_25000000", 1, 0)]
     return out
 
 
@@ -204,6 +207,25 @@ def cases(dev, n_params=N_PARAMS):
         out.append(("pull_%d" % n, "pull_kernel (%d params)" % n, 0.0, 8.0 * n,
                     lambda s, pw=pw, pd=pd, ps=ps, n=n: L.dsspk_pull(s, pd, pw, n, ps + 8, ps),
                     None, ("k_server.hip",), (w, dst, st)))
+    # the two fused server kernels at the stress size: apply + the pusher's pull in one pass (16 B/param), and four
+    # simultaneous pushes with one snapshot in one pass (4 * 4 + 8 + 4 = 28 B/param instead of 4 * 12 + 8 = 56)
+    n = 25_000_000
+    w = torch.randn(n, device=dev)
+    gs = [torch.randn(n, device=dev) * 1e-3 for _ in range(4)]
+    dst = torch.empty(n, device=dev)
+    st = torch.zeros(2, dtype=torch.int64, device=dev)
+    pw, pd, ps = w.data_ptr(), dst.data_ptr(), st.data_ptr()
+    pg = gs[0].data_ptr()
+    out.append(("apply_pull_%d" % n, "apply_pull_kernel: update + the pusher's snapshot in one pass (%d params)" % n, 0.0, 16.0 * n,
+                lambda s, pw=pw, pg=pg, pd=pd, ps=ps, n=n: L.dsspk_apply_pull(s, pw, pg, pd, n, 1e-3, ps, ps + 8, 1),
+                None, ("k_server.hip",), (w, gs, dst, st)))
+    g_arr = (ctypes.c_void_p * 4)(*[g.data_ptr() for g in gs])
+    d_arr = (ctypes.c_void_p * 1)(pd)
+    a_arr = (ctypes.c_int * 1)(4)
+    s_arr = (ctypes.c_void_p * 1)(ps + 8)
+    out.append(("apply_many4_%d" % n, "apply_many_kernel: 4 simultaneous pushes + 1 snapshot in one pass (%d params)" % n, 0.0, 28.0 * n,
+                lambda s, pw=pw, ps=ps, n=n: L.dsspk_apply_many(s, pw, 4, g_arr, n, 1e-3, 1, d_arr, a_arr, s_arr, ps, 1),
+                None, ("k_server.hip",), (w, gs, dst, st, g_arr, d_arr, a_arr, s_arr)))
     assert [c[0] for c in out] == [k for k, _, _ in case_list(n_params)]
     return out
 
