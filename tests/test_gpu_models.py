@@ -524,6 +524,39 @@ def test_graph_replay_is_bit_identical_to_eager(oracle_nn):
 
 
 # ------------------------------------------------------------------ error paths (host side; nothing faults)
+def test_failed_push_leaves_the_clocks_untouched():
+    """A push whose device half is refused (here: a gradient pointer that is not 16-byte aligned, which the launcher rejects
+    on the host before anything is enqueued) must not count: clocks, version, credits and flags stay as they were, and the
+    same push with a proper pointer then goes through."""
+    n, K = 4096, 3
+    w = torch.ones(n, device="cuda")
+    g = torch.full((n + 4,), 0.5, device="cuda")
+    snap = torch.zeros((K, n), device="cuda")
+    ctx = B.dssp_create(w, n, K, 1, 2, 0.3)
+    before = B.dssp_clock(ctx, K)
+    with pytest.raises(B.DsspError) as e:
+        B.dssp_push(ctx, 1, g[1:].data_ptr(), 5, K)
+    assert e.value.code == B.DSSP_EHIP and B.dssp_clock(ctx, K) == before
+    with pytest.raises(B.DsspError) as e:
+        B.dssp_push_pull(ctx, 1, g[1:].data_ptr(), 5, K, snap[1])
+    assert e.value.code == B.DSSP_EHIP and B.dssp_clock(ctx, K) == before
+    with pytest.raises(B.DsspError) as e:
+        B.dssp_push_many(ctx, [0, 1], [g, g[1:].data_ptr()], 5, K, [snap[q] for q in range(K)])
+    assert e.value.code == B.DSSP_EHIP and B.dssp_clock(ctx, K) == before
+    B.dssp_synchronize(ctx)
+    assert float(w.min()) == 1.0 == float(w.max())                       # and the weights were not touched
+    ok, rel, rstar, grant, pv = B.dssp_push_many(ctx, [0, 1], [g, g], 5, K, [snap[q] for q in range(K)])
+    assert ok == [True, True] and pv[:2] == [1, 2]
+    B.dssp_synchronize(ctx)
+    scale = np.float32(0.3) / np.float32(3)
+    w1 = np.float32(1.0) - scale * np.float32(0.5)
+    w2 = np.float32(w1) - scale * np.float32(0.5)
+    assert np.allclose(snap[0].cpu().numpy(), w1, rtol=0, atol=1e-7) and np.allclose(snap[1].cpu().numpy(), w2, rtol=0, atol=1e-7)
+    assert np.array_equal(w.cpu().numpy(), snap[1].cpu().numpy()) and B.dssp_device_stamps(ctx, K) == [2, 1, 2, 0]
+    B.dssp_destroy(ctx)
+
+
+
 def test_error_codes():
     import torch
     w = torch.zeros(1024, device="cuda")

@@ -164,6 +164,33 @@ def test_clock_and_state_errors_host_only():
             B.dssp_create(None, 0, *bad, 0.1)
 
 
+def test_push_many_argument_and_state_errors_leave_the_clocks_untouched():
+    K = 4
+    ctx = B.dssp_create(None, 0, K, 0, 0, 0.1)                  # BSP: whoever pushes first waits
+    none = [None] * K
+    for bad in ([1, 0], [2, 2], [0, 4], [-1, 2]):               # not ascending, repeated, out of range
+        with pytest.raises(B.DsspError) as e:
+            B.dssp_push_many(ctx, bad, [None] * len(bad), 10, K, none)
+        assert e.value.code == B.DSSP_EINVAL
+    with pytest.raises(B.DsspError) as e:
+        B.dssp_push_many(ctx, list(range(17)), [None] * 17, 10, K, none)
+    assert e.value.code == B.DSSP_EINVAL                        # more than 16 pushes in one call
+    assert B.dssp_clock(ctx, K) == ([0] * K, [0] * K, [False] * K, 0)
+    ok, rel, rstar, grant, pv = B.dssp_push_many(ctx, [0, 2], none[:2], 10, K, none)
+    assert ok == [False, False] and rel == [[], []] and pv == [0] * K
+    t, r, blocked, v = B.dssp_clock(ctx, K)
+    assert t == [1, 0, 1, 0] and blocked == [True, False, True, False] and v == 2
+    with pytest.raises(B.DsspError) as e:                       # worker 2 is waiting: nothing of the group may count
+        B.dssp_push_many(ctx, [1, 2], none[:2], 11, K, none)
+    assert e.value.code == B.DSSP_ESTATE
+    assert B.dssp_clock(ctx, K) == (t, r, blocked, v)
+    ok, rel, rstar, grant, pv = B.dssp_push_many(ctx, [1, 3], none[:2], 12, K, none)
+    assert ok == [False, True] and rel == [[], [0, 1, 2]]       # the last push of the round releases the three that waited
+    assert pv == [4, 4, 4, 4]                                   # everybody goes on with the weights after all four pushes
+    assert B.dssp_clock(ctx, K) == ([1] * K, [0] * K, [False] * K, 4)
+    B.dssp_destroy(ctx)
+
+
 def test_parameter_layout_matches_documented_one(oracle_nn):
     for model, ncls, want in [("mlp", 10, 789_258), ("alexnet_ds", 10, 1_387_786), ("alexnet_3c", 10, 1_352_714), ("resnet110", 100, 1_733_812),
                               ("resnet20", 100, None), ("resnet8", 7, None)]:
