@@ -157,6 +157,10 @@ int dsspk_add(void* stream, float* out_dev, const float* in_dev, long n);
  * maximum in scan order). */
 int dsspk_maxpool_fwd(void* stream, const float* x_dev, float* y_dev, uint8_t* arg_dev, int N, int H, int W, int C);
 int dsspk_maxpool_bwd(void* stream, const float* dy_dev, const uint8_t* arg_dev, float* dx_dev, int N, int H, int W, int C);
+/* dsspk_maxpool_bwd followed by the backward pass of the ReLU in front of the pooling, in one kernel:
+ * dx = a > 0 ? (gathered gradient) : 0, a_dev = the pooling's input (post-ReLU, dx's shape); a_dev == NULL: no mask. */
+int dsspk_maxpool_bwd_relu(void* stream, const float* dy_dev, const uint8_t* arg_dev, const float* a_dev, float* dx_dev,
+                           int N, int H, int W, int C);
 
 /* Batch normalisation over the M rows of x[M][C], batch statistics, biased variance, eps inside
  * the root.  stats: mean[C] then invstd[C] (written by fwd, read by bwd).

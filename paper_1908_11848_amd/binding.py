@@ -89,6 +89,7 @@ _SIGNATURES = {
     "dsspk_add": (c_int, [c_void_p, c_void_p, c_void_p, c_long]),
     "dsspk_maxpool_fwd": (c_int, [c_void_p] * 4 + [c_int] * 4),
     "dsspk_maxpool_bwd": (c_int, [c_void_p] * 4 + [c_int] * 4),
+    "dsspk_maxpool_bwd_relu": (c_int, [c_void_p] * 5 + [c_int] * 4),
     "dsspk_bn_fwd": (c_int, [c_void_p] * 7 + [c_long, c_int, c_float, c_int, c_int, c_void_p, c_int, c_int, c_int, c_int]),
     "dsspk_bn_bwd": (c_int, [c_void_p] * 10 + [c_long, c_int]),
     "dsspk_bn_bwd_reduce": (c_int, [c_void_p] * 6 + [c_long, c_int]),

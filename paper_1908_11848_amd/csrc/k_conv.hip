@@ -73,16 +73,24 @@ __device__ __forceinline__ bool src_pixel(const ConvGeom& g, int oh, int ow, int
 //   DGRAD: gather from dy and use the filter transposed.
 //   VEC  : IC is a multiple of 16 (one k-chunk = 16 channels of one tap, 16-byte loads);
 //          otherwise the reduction index (tap, ci) is flattened and loaded element-wise.
-template <int BM, int BN, bool DGRAD, bool VEC>
+//   KS   : k-chunks of 16 per LDS stage (VEC only; IC a multiple of 16 * KS).  A stage is one barrier, one round of
+//          address arithmetic and one round of global loads, so wide layers take KS = 2: half the barriers and
+//          half the vector instructions per MFMA (fp32 MFMA and vector arithmetic do not overlap on this chip).
+template <int BM, int BN, bool DGRAD, bool VEC, int KS = 1>
 __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
                                                              const float* __restrict__ bias, const float* __restrict__ add,
                                                              float* __restrict__ dst, ConvGeom g, int relu) {
+    static_assert(KS == 1 || VEC, "several k-chunks per stage only with 16-byte gathers");
     constexpr int WM = BM / 64, WN = BN / 16;
-    constexpr int LDB = DGRAD ? mma::LDK : BN + 4;
-    constexpr int BS = DGRAD ? BN * mma::LDK : mma::KC * (BN + 4);
+    constexpr int KST = mma::KC * KS;                              // reduction indices per stage
+    constexpr int LDA = KST + 4;                                   // pitch of a k-contiguous row: 16-byte aligned, 4 (mod 8) quads
+    constexpr int LDB = DGRAD ? LDA : BN + 4;
+    constexpr int BS = DGRAD ? BN * LDA : KST * (BN + 4);
     constexpr int RPT = BM / 64;                                   // gathered rows per thread (VEC)
-    __shared__ __attribute__((aligned(16))) float As[2][BM * mma::LDK];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BS];
+    constexpr int BV = KST * BN / 4 / THREADS > 0 ? KST * BN / 4 / THREADS : 1;     // 16-byte filter loads per thread and stage
+    extern __shared__ __attribute__((aligned(16))) float igemm_lds[];      // As[2][BM * LDA], then Bs[2][BS]
+    float (*As)[BM * LDA] = reinterpret_cast<float (*)[BM * LDA]>(igemm_lds);
+    float (*Bs)[BS] = reinterpret_cast<float (*)[BS]>(igemm_lds + 2 * BM * LDA);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long m0 = (long)blockIdx.x * BM;
     const int n0 = blockIdx.y * BN;
@@ -107,31 +115,39 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
         }
     }
 
-    float4 ra[VEC ? RPT : 1];
+    float4 ra[VEC ? RPT * KS : 1];
     float ras[VEC ? 1 : BM * mma::KC / THREADS];
-    float4 rb = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 rb[BV];
+#pragma unroll
+    for (int e = 0; e < BV; ++e) rb[e] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int ktot = taps * g.IC;
-    const int nchunks = VEC ? taps * (g.IC / mma::KC) : (ktot + mma::KC - 1) / mma::KC;
+    const int nchunks = VEC ? taps * (g.IC / KST) : (ktot + mma::KC - 1) / mma::KC;
 
     auto load = [&](int chunk) {
         if constexpr (VEC) {
-            const int cpt = g.IC / mma::KC;
-            const int tap = chunk / cpt, c0 = (chunk - tap * cpt) * mma::KC;
+            const int cpt = g.IC / KST;
+            const int tap = chunk / cpt, c0 = (chunk - tap * cpt) * KST;
             const int kh = tap / g.KW, kw = tap - kh * g.KW;
 #pragma unroll
             for (int e = 0; e < RPT; ++e) {
                 int sh, sw;
                 const bool ok = rvalid[e] && src_pixel<DGRAD>(g, roh[e], row_w[e], kh, kw, sh, sw);
-                ra[e] = ok ? *reinterpret_cast<const float4*>(src + (((long)rn[e] * g.SH + sh) * g.SW + sw) * g.IC + c0 + 4 * part)
-                           : make_float4(0.f, 0.f, 0.f, 0.f);
+                const float* sp = src + (((long)rn[e] * g.SH + sh) * g.SW + sw) * g.IC + c0 + 4 * part;
+#pragma unroll
+                for (int u = 0; u < KS; ++u)
+                    ra[e * KS + u] = ok ? *reinterpret_cast<const float4*>(sp + mma::KC * u) : make_float4(0.f, 0.f, 0.f, 0.f);
             }
-            if (tid < 4 * BN) {
-                if constexpr (!DGRAD) {       // rows k = channel c0+k of this tap, BN columns
-                    const int k = tid / (BN / 4), j4 = tid % (BN / 4);
-                    rb = *reinterpret_cast<const float4*>(wgt + ((long)tap * g.IC + c0 + k) * g.OC + n0 + 4 * j4);
-                } else {                      // rows j = result channel, 16 contiguous reduction channels
-                    const int j = tid >> 2;
-                    rb = *reinterpret_cast<const float4*>(wgt + ((long)tap * g.OC + n0 + j) * g.IC + c0 + 4 * part);
+#pragma unroll
+            for (int e = 0; e < BV; ++e) {
+                const int idx = tid + e * THREADS;
+                if (idx < KST * BN / 4) {
+                    if constexpr (!DGRAD) {   // rows k = channel c0+k of this tap, BN columns
+                        const int k = idx / (BN / 4), j4 = idx % (BN / 4);
+                        rb[e] = *reinterpret_cast<const float4*>(wgt + ((long)tap * g.IC + c0 + k) * g.OC + n0 + 4 * j4);
+                    } else {                  // rows j = result channel, KST contiguous reduction channels
+                        const int j = idx / (KST / 4), k4 = idx % (KST / 4);
+                        rb[e] = *reinterpret_cast<const float4*>(wgt + ((long)tap * g.OC + n0 + j) * g.IC + c0 + 4 * k4);
+                    }
                 }
             }
         } else {
@@ -155,8 +171,8 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
             }
             if (tid < 4 * BN) {               // forward only: filter rows are the flattened (tap, ci)
                 const int k = tid / (BN / 4), j4 = tid % (BN / 4);
-                rb = (k0 + k < ktot) ? *reinterpret_cast<const float4*>(wgt + (long)(k0 + k) * g.OC + n0 + 4 * j4)
-                                     : make_float4(0.f, 0.f, 0.f, 0.f);
+                rb[0] = (k0 + k < ktot) ? *reinterpret_cast<const float4*>(wgt + (long)(k0 + k) * g.OC + n0 + 4 * j4)
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
     };
@@ -164,21 +180,33 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
         if constexpr (VEC) {
 #pragma unroll
             for (int e = 0; e < RPT; ++e)
-                *reinterpret_cast<float4*>(&As[buf][((tid >> 2) + 64 * e) * mma::LDK + 4 * part]) = ra[e];
+#pragma unroll
+                for (int u = 0; u < KS; ++u)
+                    *reinterpret_cast<float4*>(&As[buf][((tid >> 2) + 64 * e) * LDA + mma::KC * u + 4 * part]) = ra[e * KS + u];
         } else {
 #pragma unroll
             for (int e = 0; e < BM * mma::KC / THREADS; ++e) {
                 const int idx = tid + e * THREADS;
-                As[buf][(idx / mma::KC) * mma::LDK + idx % mma::KC] = ras[e];
+                As[buf][(idx / mma::KC) * LDA + idx % mma::KC] = ras[e];
             }
         }
-        if (tid < 4 * BN) {
-            if constexpr (!DGRAD) {
-                const int k = tid / (BN / 4), j4 = tid % (BN / 4);
-                *reinterpret_cast<float4*>(&Bs[buf][k * LDB + 4 * j4]) = rb;
-            } else {
-                *reinterpret_cast<float4*>(&Bs[buf][(tid >> 2) * LDB + 4 * part]) = rb;
+        if constexpr (VEC) {
+#pragma unroll
+            for (int e = 0; e < BV; ++e) {
+                const int idx = tid + e * THREADS;
+                if (idx < KST * BN / 4) {
+                    if constexpr (!DGRAD) {
+                        const int k = idx / (BN / 4), j4 = idx % (BN / 4);
+                        *reinterpret_cast<float4*>(&Bs[buf][k * LDB + 4 * j4]) = rb[e];
+                    } else {
+                        const int j = idx / (KST / 4), k4 = idx % (KST / 4);
+                        *reinterpret_cast<float4*>(&Bs[buf][j * LDB + 4 * k4]) = rb[e];
+                    }
+                }
             }
+        } else if (tid < 4 * BN) {
+            const int k = tid / (BN / 4), j4 = tid % (BN / 4);
+            *reinterpret_cast<float4*>(&Bs[buf][k * LDB + 4 * j4]) = rb[0];
         }
     };
 
@@ -188,7 +216,10 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
         store(buf);
         __syncthreads();
         if (c + 1 < nchunks) load(c + 1);
-        mma::chunk16<WM, WN, false, DGRAD>(As[buf], mma::LDK, Bs[buf], LDB, wave * (BM / 4), 0, acc, lane);
+#pragma unroll
+        for (int u = 0; u < KS; ++u)
+            mma::chunk16<WM, WN, false, DGRAD>(As[buf] + mma::KC * u, LDA, Bs[buf] + (DGRAD ? mma::KC * u : mma::KC * u * LDB), LDB,
+                                               wave * (BM / 4), 0, acc, lane);
     }
 
     mma::drain();
@@ -458,6 +489,29 @@ int wgrad_stages(const ConvGeom& g, int grid_y) {
     return (int)s;
 }
 
+// LDS of an instantiation (floats), as laid out in the kernel
+template <int BM, int BN, bool DGRAD, int KS>
+constexpr size_t igemm_lds_bytes() {
+    constexpr int KST = mma::KC * KS, LDA = KST + 4;
+    return sizeof(float) * 2 * ((size_t)BM * LDA + (DGRAD ? (size_t)BN * LDA : (size_t)KST * (BN + 4)));
+}
+
+template <int BM, int BN, bool DGRAD, bool VEC, int KS>
+int igemm_launch(dim3 grid, hipStream_t s, const float* src, const float* w, const float* bias, const float* add, float* dst,
+                 const ConvGeom& g, int relu) {
+    constexpr size_t bytes = igemm_lds_bytes<BM, BN, DGRAD, KS>();
+    auto kern = conv_igemm_kernel<BM, BN, DGRAD, VEC, KS>;
+    static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
+    if (!attr_set) {
+        if (bytes > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+            return -1;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(THREADS), bytes, s, src, w, bias, add, dst, g, relu);
+    return 0;
+}
+
 template <bool DGRAD, bool VEC>
 int launch_igemm(hipStream_t s, const float* src, const float* w, const float* bias, const float* add, float* dst, const ConvGeom& g, int relu) {
     // output-channel tile: the widest of 64, 32, 16 that divides the layer
@@ -466,9 +520,21 @@ int launch_igemm(hipStream_t s, const float* src, const float* w, const float* b
     // small problems take 64-pixel tiles so that the grid still covers the chip
     const bool small = g.M < 128L * 512;
     dim3 grid(ceil_div(g.M, small ? 64 : 128), g.OC / bn);
-#define GO(BM, BN) hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, DGRAD, VEC>), grid, dim3(THREADS), 0, s, src, w, bias, add, dst, g, relu)
+#define GO(BM, BN) do { if (igemm_launch<BM, BN, DGRAD, VEC, 1>(grid, s, src, w, bias, add, dst, g, relu)) return -1; } while (0)
+#define GOK(BM, BN, KS) do { if (igemm_launch<BM, BN, DGRAD, VEC, KS>(grid, s, src, w, bias, add, dst, g, relu)) return -1; } while (0)
+    if constexpr (VEC) {
+        if (bn == 64 && g.IC % 64 == 0 && small) {      // wide layers: several k-chunks per stage
+            GOK(64, 64, 4);
+            return DSSPK_LAUNCH_RC();
+        }
+        if (bn == 64 && g.IC % 32 == 0) {
+            if (small) GOK(64, 64, 2); else GOK(128, 64, 2);
+            return DSSPK_LAUNCH_RC();
+        }
+    }
     if (small) { if (bn == 16) GO(64, 16); else if (bn == 32) GO(64, 32); else GO(64, 64); }
     else       { if (bn == 16) GO(128, 16); else if (bn == 32) GO(128, 32); else GO(128, 64); }
+#undef GOK
 #undef GO
     return DSSPK_LAUNCH_RC();
 }

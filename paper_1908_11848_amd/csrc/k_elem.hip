@@ -92,6 +92,70 @@ __global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const float* __res
     }
 }
 
+// The same two kernels for channel counts that are multiples of 4 and tensors below 2^31 elements (every shape the
+// networks here have): a lane owns 4 channels of one pixel (16-byte loads and stores, the four choices in one 4-byte
+// word) and all index arithmetic is 32-bit (a 64-bit division per element costs more than the memory traffic).
+// MASK: the backward kernel also applies the ReLU that precedes the pooling, dx = a > 0 ? gathered gradient : 0
+// (a = the pooling's input, a post-ReLU activation), which saves a pass over dx.
+__global__ __launch_bounds__(THREADS) void maxpool_fwd4_kernel(const float4* __restrict__ x, float4* __restrict__ y,
+                                                               uchar4* __restrict__ arg, int H, int W, int C4, int Ho, int Wo, unsigned total) {
+    for (unsigned i = blockIdx.x * THREADS + threadIdx.x; i < total; i += gridDim.x * THREADS) {
+        const unsigned c = i % (unsigned)C4;
+        unsigned r = i / (unsigned)C4;
+        const unsigned wo = r % (unsigned)Wo; r /= (unsigned)Wo;
+        const unsigned ho = r % (unsigned)Ho;
+        const unsigned n = r / (unsigned)Ho;
+        const float4* base = x + ((size_t)(n * H + 2 * ho) * W + 2 * wo) * C4 + c;
+        float4 v[9];
+#pragma unroll
+        for (int k = 0; k < 9; ++k) v[k] = base[(size_t)((k / 3) * W + (k % 3)) * C4];
+        float4 best = v[0];
+        uchar4 bi = make_uchar4(0, 0, 0, 0);
+#pragma unroll
+        for (int k = 1; k < 9; ++k) {        // first maximum in scan order, per channel
+            if (v[k].x > best.x) { best.x = v[k].x; bi.x = (unsigned char)k; }
+            if (v[k].y > best.y) { best.y = v[k].y; bi.y = (unsigned char)k; }
+            if (v[k].z > best.z) { best.z = v[k].z; bi.z = (unsigned char)k; }
+            if (v[k].w > best.w) { best.w = v[k].w; bi.w = (unsigned char)k; }
+        }
+        y[i] = best;
+        arg[i] = bi;
+    }
+}
+
+template <bool MASK>
+__global__ __launch_bounds__(THREADS) void maxpool_bwd4_kernel(const float4* __restrict__ dy, const uchar4* __restrict__ arg,
+                                                               const float4* __restrict__ a, float4* __restrict__ dx, int H, int W,
+                                                               int C4, int Ho, int Wo, unsigned total) {
+    for (unsigned i = blockIdx.x * THREADS + threadIdx.x; i < total; i += gridDim.x * THREADS) {
+        const unsigned c = i % (unsigned)C4;
+        unsigned r = i / (unsigned)C4;
+        const int wi = (int)(r % (unsigned)W); r /= (unsigned)W;
+        const int hi = (int)(r % (unsigned)H);
+        const unsigned n = r / (unsigned)H;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int ho_lo = hi >= 2 ? (hi - 1) / 2 : 0, ho_hi = min(Ho - 1, hi / 2);
+        const int wo_lo = wi >= 2 ? (wi - 1) / 2 : 0, wo_hi = min(Wo - 1, wi / 2);
+        for (int ho = ho_lo; ho <= ho_hi; ++ho)           // same window order as the scalar kernel: sums are identical
+            for (int wo = wo_lo; wo <= wo_hi; ++wo) {
+                const size_t o = ((size_t)(n * Ho + ho) * Wo + wo) * C4 + c;
+                const unsigned char want = (unsigned char)((hi - 2 * ho) * 3 + (wi - 2 * wo));
+                const uchar4 ch = arg[o];
+                const float4 g = dy[o];
+                if (ch.x == want) s.x += g.x;
+                if (ch.y == want) s.y += g.y;
+                if (ch.z == want) s.z += g.z;
+                if (ch.w == want) s.w += g.w;
+            }
+        if constexpr (MASK) {
+            const float4 av = a[i];
+            s.x = av.x > 0.f ? s.x : 0.f; s.y = av.y > 0.f ? s.y : 0.f;
+            s.z = av.z > 0.f ? s.z : 0.f; s.w = av.w > 0.f ? s.w : 0.f;
+        }
+        dx[i] = s;
+    }
+}
+
 // ------------------------------------------------------------------ batch normalisation
 // Two kernels per direction, no cross-workgroup synchronisation:
 //   forward : (1) per slab of rows, mean and sum of squared deviations per channel;
@@ -424,17 +488,41 @@ extern "C" int dsspk_add(void* stream, float* out, const float* in, long n) {
 extern "C" int dsspk_maxpool_fwd(void* stream, const float* x, float* y, uint8_t* arg, int N, int H, int W, int C) {
     if (!x || !y || !arg || N < 1 || H < 3 || W < 3 || C < 1) return -1;
     const int Ho = (H - 3) / 2 + 1, Wo = (W - 3) / 2 + 1;
+    if (C % 4 == 0 && (long)N * H * W * C < (1L << 31) && al16(x) && al16(y) && (reinterpret_cast<uintptr_t>(arg) & 3) == 0) {
+        const long total = (long)N * Ho * Wo * (C / 4);
+        hipLaunchKernelGGL(maxpool_fwd4_kernel, dim3(grid_for(total)), dim3(THREADS), 0, (hipStream_t)stream,
+                           reinterpret_cast<const float4*>(x), reinterpret_cast<float4*>(y), reinterpret_cast<uchar4*>(arg), H, W, C / 4,
+                           Ho, Wo, (unsigned)total);
+        return DSSPK_LAUNCH_RC();
+    }
     hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for((long)N * Ho * Wo * C)), dim3(THREADS), 0, (hipStream_t)stream,
                        x, y, arg, N, H, W, C, Ho, Wo);
     return DSSPK_LAUNCH_RC();
 }
 
-extern "C" int dsspk_maxpool_bwd(void* stream, const float* dy, const uint8_t* arg, float* dx, int N, int H, int W, int C) {
+extern "C" int dsspk_maxpool_bwd_relu(void* stream, const float* dy, const uint8_t* arg, const float* a, float* dx, int N, int H,
+                                      int W, int C) {
     if (!dy || !dx || !arg || N < 1 || H < 3 || W < 3 || C < 1) return -1;
     const int Ho = (H - 3) / 2 + 1, Wo = (W - 3) / 2 + 1;
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for((long)N * H * W * C)), dim3(THREADS), 0, (hipStream_t)stream,
-                       dy, arg, dx, N, H, W, C, Ho, Wo);
-    return DSSPK_LAUNCH_RC();
+    hipStream_t s = (hipStream_t)stream;
+    if (C % 4 == 0 && (long)N * H * W * C < (1L << 31) && al16(dy) && al16(dx) && (!a || al16(a)) && (reinterpret_cast<uintptr_t>(arg) & 3) == 0) {
+        const long total = (long)N * H * W * (C / 4);
+        const float4* a4 = reinterpret_cast<const float4*>(a);
+        if (a)
+            hipLaunchKernelGGL((maxpool_bwd4_kernel<true>), dim3(grid_for(total)), dim3(THREADS), 0, s, reinterpret_cast<const float4*>(dy),
+                               reinterpret_cast<const uchar4*>(arg), a4, reinterpret_cast<float4*>(dx), H, W, C / 4, Ho, Wo, (unsigned)total);
+        else
+            hipLaunchKernelGGL((maxpool_bwd4_kernel<false>), dim3(grid_for(total)), dim3(THREADS), 0, s, reinterpret_cast<const float4*>(dy),
+                               reinterpret_cast<const uchar4*>(arg), a4, reinterpret_cast<float4*>(dx), H, W, C / 4, Ho, Wo, (unsigned)total);
+        return DSSPK_LAUNCH_RC();
+    }
+    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for((long)N * H * W * C)), dim3(THREADS), 0, s, dy, arg, dx, N, H, W, C, Ho, Wo);
+    if (int rc = DSSPK_LAUNCH_RC()) return rc;
+    return a ? dsspk_relu_bwd(stream, dx, a, (long)N * H * W * C) : 0;
+}
+
+extern "C" int dsspk_maxpool_bwd(void* stream, const float* dy, const uint8_t* arg, float* dx, int N, int H, int W, int C) {
+    return dsspk_maxpool_bwd_relu(stream, dy, arg, nullptr, dx, N, H, W, C);
 }
 
 extern "C" size_t dsspk_bn_scratch_floats(long M, int C) {

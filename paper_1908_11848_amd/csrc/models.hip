@@ -236,13 +236,11 @@ int step_alexnet(Plan* P, char* ws, void* s, const float* x, const int32_t* y, c
     RUN(dsspk_gemm(s, p2, 1, 3136, da3, 384, 1, g + fw1, 384, 3136, 384, m, nullptr, 0));
     RUN(dsspk_colsum(s, da3, g + fb1, nullptr, m, 384));
     RUN(dsspk_gemm(s, da3, 384, 1, w + fw1, 1, 384, dp2, 3136, m, 3136, 384, nullptr, 0));
-    RUN(dsspk_maxpool_bwd(s, dp2, arg2, da2, m, 15, 15, 64));
-    RUN(dsspk_relu_bwd(s, da2, a2, (long)m * 15 * 15 * 64));
+    RUN(dsspk_maxpool_bwd_relu(s, dp2, arg2, a2, da2, m, 15, 15, 64));
     RUN(dsspk_conv_bwd_weight(s, p1, da2, g + cw2, scr, m, 15, 15, 64, 64, 5, 5, 1, 2));
     RUN(dsspk_colsum(s, da2, g + cb2, F(P->colsum_scratch), (long)m * 15 * 15, 64));
     RUN(dsspk_conv_bwd_data(s, da2, w + cw2, nullptr, dp1, m, 15, 15, 64, 64, 5, 5, 1, 2));
-    RUN(dsspk_maxpool_bwd(s, dp1, arg1, da1, m, 32, 32, 64));
-    RUN(dsspk_relu_bwd(s, da1, a1, (long)m * 32 * 32 * 64));
+    RUN(dsspk_maxpool_bwd_relu(s, dp1, arg1, a1, da1, m, 32, 32, 64));
     RUN(dsspk_conv_bwd_weight(s, x, da1, g + cw1, scr, m, 32, 32, 3, 64, 5, 5, 1, 2));
     RUN(dsspk_colsum(s, da1, g + cb1, F(P->colsum_scratch), (long)m * 32 * 32, 64));
     return 0;
@@ -281,13 +279,11 @@ int step_alexnet3(Plan* P, char* ws, void* s, const float* x, const int32_t* y, 
     RUN(dsspk_conv_bwd_weight(s, p2, dc3, g + cw3, scr, m, 7, 7, 64, 64, 3, 3, 1, 1));
     RUN(dsspk_colsum(s, dc3, g + cb3, cscr, (long)m * 7 * 7, 64));
     RUN(dsspk_conv_bwd_data(s, dc3, w + cw3, nullptr, dp2, m, 7, 7, 64, 64, 3, 3, 1, 1));
-    RUN(dsspk_maxpool_bwd(s, dp2, arg2, da2, m, 15, 15, 64));
-    RUN(dsspk_relu_bwd(s, da2, a2, (long)m * 15 * 15 * 64));
+    RUN(dsspk_maxpool_bwd_relu(s, dp2, arg2, a2, da2, m, 15, 15, 64));
     RUN(dsspk_conv_bwd_weight(s, p1, da2, g + cw2, scr, m, 15, 15, 64, 64, 5, 5, 1, 2));
     RUN(dsspk_colsum(s, da2, g + cb2, cscr, (long)m * 15 * 15, 64));
     RUN(dsspk_conv_bwd_data(s, da2, w + cw2, nullptr, dp1, m, 15, 15, 64, 64, 5, 5, 1, 2));
-    RUN(dsspk_maxpool_bwd(s, dp1, arg1, da1, m, 32, 32, 64));
-    RUN(dsspk_relu_bwd(s, da1, a1, (long)m * 32 * 32 * 64));
+    RUN(dsspk_maxpool_bwd_relu(s, dp1, arg1, a1, da1, m, 32, 32, 64));
     RUN(dsspk_conv_bwd_weight(s, x, da1, g + cw1, scr, m, 32, 32, 3, 64, 5, 5, 1, 2));
     RUN(dsspk_colsum(s, da1, g + cb1, cscr, (long)m * 32 * 32, 64));
     return 0;

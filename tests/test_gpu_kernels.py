@@ -544,8 +544,8 @@ def test_relu_bwd_and_add(n):
     assert np.array_equal(host(DY)[:n], got[:n] + a[:n])
 
 
-@pytest.mark.parametrize("N,H,C", [(2, 32, 64), (3, 15, 64), (1, 5, 4), (128, 15, 64)])
-def test_maxpool(oracle_nn, N, H, C):
+@pytest.mark.parametrize("N,H,C", [(2, 32, 64), (3, 15, 64), (1, 5, 4), (128, 15, 64), (2, 9, 6), (1, 4, 3)])
+def test_maxpool(oracle_nn, N, H, C):        # C = 6, 3: channel counts the 16-byte kernels do not take (scalar kernels)
     g = np.random.default_rng(H)
     x = f32(g, (N, H, H, C))
     Ho = (H - 3) // 2 + 1
@@ -559,6 +559,10 @@ def test_maxpool(oracle_nn, N, H, C):
     assert np.array_equal(host(y).astype(np.float64), yo)
     dxo = oracle_nn.maxpool_bwd(dy.astype(np.float64), argo, x.shape, 3, 2)
     assert rel_l2(host(dx), dxo) < TOL
+    # with the backward pass of the ReLU in front of the pooling folded in (mask from the pooling's input)
+    dxm = empty((N, H, H, C))
+    rc(B.lib().dsspk_maxpool_bwd_relu(stream_ptr(), DY.data_ptr(), arg.data_ptr(), X.data_ptr(), dxm.data_ptr(), N, H, H, C))
+    assert np.array_equal(host(dxm), np.where(x > 0, host(dx), np.float32(0)))
 
 
 # ------------------------------------------------------------------ batch normalisation (+ shortcut, ReLU)
