@@ -47,6 +47,16 @@ struct ConvGeom {
     long M;             // N * OH * OW
 };
 
+// Row m of the GEMM -> (image, output row, output column).  M < 2^31 (checked when the geometry is built), so the
+// divisions are 32-bit: a 64-bit division per gathered element costs more than the element's memory traffic.
+__device__ __forceinline__ void row_pixel(const ConvGeom& g, long m, int& n, int& oh, int& ow) {
+    const unsigned mu = (unsigned)m, W = (unsigned)g.OW, H = (unsigned)g.OH;
+    const unsigned r = mu / W;
+    ow = (int)(mu - r * W);
+    n = (int)(r / H);
+    oh = (int)(r - (unsigned)n * H);
+}
+
 // Source pixel of row-pixel (oh, ow) for filter tap (kh, kw); false if it falls into the padding
 // (forward) or between the strides (d-input).
 template <bool DGRAD>
@@ -109,12 +119,22 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
             const long m = m0 + (tid >> 2) + 64 * e;
             rvalid[e] = m < g.M;
             const long mm = rvalid[e] ? m : 0;
-            row_w[e] = (int)(mm % g.OW);
-            roh[e] = (int)((mm / g.OW) % g.OH);
-            rn[e] = (int)(mm / ((long)g.OW * g.OH));
+            row_pixel(g, mm, rn[e], roh[e], row_w[e]);
         }
     }
 
+    // element-wise gather (!VEC): thread t loads reduction index t % 16 of rows t / 16 + 16 e, the same rows in every chunk
+    constexpr int EPT = BM * mma::KC / THREADS;
+    int sn[VEC ? 1 : EPT], soh[VEC ? 1 : EPT], sow[VEC ? 1 : EPT];
+    if constexpr (!VEC) {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const long m = m0 + (tid >> 4) + 16 * e;
+            const long mm = m < g.M ? m : 0;
+            row_pixel(g, mm, sn[e], soh[e], sow[e]);
+            if (m >= g.M) sn[e] = -1;
+        }
+    }
     float4 ra[VEC ? RPT * KS : 1];
     float ras[VEC ? 1 : BM * mma::KC / THREADS];
     float4 rb[BV];
@@ -152,21 +172,15 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
             }
         } else {
             const int k0 = chunk * mma::KC;
+            const int kk = k0 + (tid & 15);
+            const int tap = kk / g.IC, ci = kk - tap * g.IC;
+            const int kh = tap / g.KW, kw = tap - kh * g.KW;
 #pragma unroll
-            for (int e = 0; e < BM * mma::KC / THREADS; ++e) {
-                const int idx = tid + e * THREADS;
-                const int row = idx / mma::KC, k = idx % mma::KC;
-                const long m = m0 + row;
-                const int kk = k0 + k;
+            for (int e = 0; e < EPT; ++e) {
                 float v = 0.f;
-                if (m < g.M && kk < ktot) {
-                    const int tap = kk / g.IC, ci = kk - tap * g.IC;
-                    const int kh = tap / g.KW, kw = tap - kh * g.KW;
-                    const int ow = (int)(m % g.OW), oh = (int)((m / g.OW) % g.OH), n = (int)(m / ((long)g.OW * g.OH));
-                    int sh, sw;
-                    if (src_pixel<DGRAD>(g, oh, ow, kh, kw, sh, sw))
-                        v = src[(((long)n * g.SH + sh) * g.SW + sw) * g.IC + ci];
-                }
+                int sh, sw;
+                if (sn[e] >= 0 && kk < ktot && src_pixel<DGRAD>(g, soh[e], sow[e], kh, kw, sh, sw))
+                    v = src[(((long)sn[e] * g.SH + sh) * g.SW + sw) * g.IC + ci];
                 ras[e] = v;
             }
             if (tid < 4 * BN) {               // forward only: filter rows are the flattened (tap, ci)
@@ -279,7 +293,8 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
                 const long m = p0 + pix;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (m < g.M) {
-                    const int ow = (int)(m % g.OW), oh = (int)((m / g.OW) % g.OH), n = (int)(m / ((long)g.OW * g.OH));
+                    int n, oh, ow;
+                    row_pixel(g, m, n, oh, ow);
                     int sh, sw;
                     if (src_pixel<false>(g, oh, ow, kh, kw, sh, sw))
                         v = *reinterpret_cast<const float4*>(x + (((long)n * g.SH + sh) * g.SW + sw) * g.IC + ci0 + 4 * c4);
@@ -294,7 +309,8 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
                 if (m < g.M && kk < rows_total) {
                     const int t2 = kk / g.IC, ci = kk - t2 * g.IC;
                     const int kh2 = t2 / g.KW, kw2 = t2 - kh2 * g.KW;
-                    const int ow = (int)(m % g.OW), oh = (int)((m / g.OW) % g.OH), n = (int)(m / ((long)g.OW * g.OH));
+                    int n, oh, ow;
+                    row_pixel(g, m, n, oh, ow);
                     int sh, sw;
                     if (src_pixel<false>(g, oh, ow, kh2, kw2, sh, sw))
                         v = x[(((long)n * g.SH + sh) * g.SW + sw) * g.IC + ci];
@@ -381,7 +397,8 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_tile_kernel(const float* _
             const long m = p0 + pix;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (m < g.M) {
-                const int ow = (int)(m % g.OW), oh = (int)((m / g.OW) % g.OH), n = (int)(m / ((long)g.OW * g.OH));
+                int n, oh, ow;
+                    row_pixel(g, m, n, oh, ow);
                 int sh, sw;
                 if (src_pixel<false>(g, oh, ow, kh, kw, sh, sw))
                     v = *reinterpret_cast<const float4*>(x + (((long)n * g.SH + sh) * g.SW + sw) * g.IC + 4 * c4);
@@ -477,7 +494,7 @@ bool geom(ConvGeom& g, int N, int H, int W, int Cin, int Cout, int KH, int KW, i
     g.OH = (H + 2 * pad - KH) / stride + 1;
     g.OW = (W + 2 * pad - KW) / stride + 1;
     g.M = (long)N * g.OH * g.OW;
-    return true;
+    return g.M < (1L << 31);
 }
 
 int wgrad_stages(const ConvGeom& g, int grid_y) {
@@ -590,6 +607,7 @@ extern "C" int dsspk_conv_bwd_data(void* stream, const float* dy, const float* w
     ConvGeom g = f;                       // rows: input pixels; gathered tensor: dy
     g.OH = H; g.OW = W; g.SH = f.OH; g.SW = f.OW; g.IC = Cout; g.OC = Cin;
     g.M = (long)N * H * W;
+    if (g.M >= (1L << 31)) return -1;
     return launch_igemm<true, true>((hipStream_t)stream, dy, w, nullptr, add, dx, g, 0);
 }
 
