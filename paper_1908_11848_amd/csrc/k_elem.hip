@@ -228,7 +228,7 @@ __global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restri
     __shared__ __attribute__((aligned(16))) float sh[2 * THREADS];
     bn_merge_stats(partial, M, C, eps, red, sh, L);
     if (blockIdx.x == 0 && threadIdx.x < 2 * C) stats[threadIdx.x] = sh[threadIdx.x];
-    const int VC = C / 4;
+    const int VC = C / 4, vshift = __ffs(VC) - 1;
     const long total = M * VC;
     const long stride = (long)gridDim.x * THREADS;
     // four independent rows per lane and trip: all loads are issued before the first use
@@ -239,17 +239,18 @@ __global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restri
         for (int u = 0; u < 4; ++u) {
             const long i = i0 + u * stride;
             ok[u] = i < total;
-            const int vc = (int)(i % VC);
-            const long row = i / VC;
+            const int vc = (int)(i & (VC - 1));     // VC is a power of two (C is 4 .. 64 and divides the workgroup size)
+            const long row = i >> vshift;
             v[u] = ok[u] ? *reinterpret_cast<const float4*>(x + row * C + 4 * vc) : make_float4(0.f, 0.f, 0.f, 0.f);
             s4[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             if constexpr (SC_MODE == 1) {
                 if (ok[u]) s4[u] = *reinterpret_cast<const float4*>(sc + row * C + 4 * vc);
             } else if constexpr (SC_MODE == 2) {
                 if (ok[u] && 4 * vc < C / 2) {   // first half of the channels: input pixel (2ho, 2wo), C/2 channels wide
-                    const int wo = (int)(row % sc_wo);
-                    const int ho = (int)((row / sc_wo) % sc_ho);
-                    const long n = row / ((long)sc_wo * sc_ho);
+                    const unsigned ru = (unsigned)row, rq = ru / (unsigned)sc_wo;       // M < 2^31: 32-bit divisions
+                    const int wo = (int)(ru - rq * (unsigned)sc_wo);
+                    const long n = rq / (unsigned)sc_ho;
+                    const int ho = (int)(rq - (unsigned)n * (unsigned)sc_ho);
                     s4[u] = *reinterpret_cast<const float4*>(sc + ((n * (2 * sc_ho) + 2 * ho) * (2 * sc_wo) + 2 * wo) * (C / 2) + 4 * vc);
                 }
             }
@@ -258,8 +259,8 @@ __global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restri
         for (int u = 0; u < 4; ++u) {
             if (!ok[u]) continue;
             const long i = i0 + u * stride;
-            const int vc = (int)(i % VC);
-            const long row = i / VC;
+            const int vc = (int)(i & (VC - 1));     // VC is a power of two (C is 4 .. 64 and divides the workgroup size)
+            const long row = i >> vshift;
             const float4 mu = *reinterpret_cast<const float4*>(sh + 4 * vc);
             const float4 is = *reinterpret_cast<const float4*>(sh + C + 4 * vc);
             const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
@@ -352,7 +353,7 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restr
         }
         __syncthreads();
     }
-    const int VC = C / 4;
+    const int VC = C / 4, vshift = __ffs(VC) - 1;
     const long total = M * VC;
     const float inv_m = 1.0f / (float)M;
     const long stride = (long)gridDim.x * THREADS;
@@ -363,8 +364,8 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restr
         for (int u = 0; u < 4; ++u) {            // all loads of the trip first
             const long i = i0 + u * stride;
             ok[u] = i < total;
-            const int vc = (int)(i % VC);
-            const long row = i / VC;
+            const int vc = (int)(i & (VC - 1));     // VC is a power of two (C is 4 .. 64 and divides the workgroup size)
+            const long row = i >> vshift;
             v[u] = ok[u] ? *reinterpret_cast<const float4*>(x + row * C + 4 * vc) : make_float4(0.f, 0.f, 0.f, 0.f);
             d[u] = ok[u] ? *reinterpret_cast<const float4*>(dz + row * C + 4 * vc) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
@@ -372,8 +373,8 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_dx_kernel(const float* __restr
         for (int u = 0; u < 4; ++u) {
             if (!ok[u]) continue;
             const long i = i0 + u * stride;
-            const int vc = (int)(i % VC);
-            const long row = i / VC;
+            const int vc = (int)(i & (VC - 1));     // VC is a power of two (C is 4 .. 64 and divides the workgroup size)
+            const long row = i >> vshift;
             const float4 mu = *reinterpret_cast<const float4*>(stats + 4 * vc);
             const float4 is = *reinterpret_cast<const float4*>(stats + C + 4 * vc);
             const float4 ga = *reinterpret_cast<const float4*>(gamma + 4 * vc);
@@ -469,7 +470,7 @@ __global__ void softmax_xent_kernel(const float* __restrict__ z, const int32_t* 
 
 inline int grid_for(long items) { return stream_grid(ceil_div(items, THREADS)); }
 inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
-inline bool bn_ok(long M, int C) { return M >= 1 && C >= 4 && C % 4 == 0 && C <= 64 && THREADS % C == 0; }
+inline bool bn_ok(long M, int C) { return M >= 1 && M < (1L << 31) && C >= 4 && C % 4 == 0 && C <= 64 && THREADS % C == 0; }
 
 }  // namespace
 
