@@ -56,8 +56,7 @@ PYTEST_CONFIG = None        # set by conftest.pytest_configure
 
 
 def progress(msg):
-    """One line that reaches the terminal even while pytest captures output (a long oracle run must not look hung),
-    and a copy in a log file next to the other run outputs."""
+    """One line that reaches the terminal even while pytest captures output (a long oracle run must not look hung)."""
     line = "[%6.0fs] %s" % (time.time() - _T0, msg)
     capman = PYTEST_CONFIG.pluginmanager.getplugin("capturemanager") if PYTEST_CONFIG is not None else None
     if capman is not None:
@@ -65,13 +64,14 @@ def progress(msg):
             print(line, file=sys.stderr, flush=True)
     else:
         print(line, file=sys.stderr, flush=True)
-    try:
-        d = os.path.join(ROOT, "gpurun_out")
-        os.makedirs(d, exist_ok=True)
-        with open(os.path.join(d, "test_progress.log"), "a") as f:
-            f.write(line + "\n")
-    except OSError:
-        pass
+    d = os.environ.get("DSSP_TEST_PROGRESS_DIR")        # optionally also into a file of the caller's choosing
+    if d:
+        try:
+            os.makedirs(d, exist_ok=True)
+            with open(os.path.join(d, "test_progress.log"), "a") as f:
+                f.write(line + "\n")
+        except OSError:
+            pass
 
 
 MARGIN_FACTOR = 8.0         # a decision may differ only where the oracle's margin is within this many forward errors
