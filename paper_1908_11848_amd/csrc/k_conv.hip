@@ -38,6 +38,8 @@ int conv3x3_tiled_dgrad_bn_wgrad(hipStream_t s, const float* dz, const float* xc
 namespace {
 
 constexpr int THREADS = 256;
+constexpr int IGEMM_IMG_MAX = 2048;                 // floats of the staged input rows (element-wise forward gather)
+constexpr int IGEMM_STAGED = 1, IGEMM_PARITY = 2;   // gather modes of conv_igemm_kernel
 
 struct ConvGeom {
     int N, OH, OW;      // pixel grid of the GEMM's rows
@@ -69,7 +71,10 @@ __device__ __forceinline__ bool src_pixel(const ConvGeom& g, int oh, int ow, int
         const int hs = oh + g.pad - kh, ws = ow + g.pad - kw;
         if (hs < 0 || ws < 0) return false;
         if (g.stride == 1) { sh = hs; sw = ws; }
-        else {
+        else if (g.stride == 2) {                      // the usual down-sampling stride: no division per gathered row
+            if ((hs | ws) & 1) return false;
+            sh = hs >> 1; sw = ws >> 1;
+        } else {
             if ((hs % g.stride) | (ws % g.stride)) return false;
             sh = hs / g.stride; sw = ws / g.stride;
         }
@@ -89,7 +94,7 @@ __device__ __forceinline__ bool src_pixel(const ConvGeom& g, int oh, int ow, int
 template <int BM, int BN, bool DGRAD, bool VEC, int KS = 1>
 __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __restrict__ src, const float* __restrict__ wgt,
                                                              const float* __restrict__ bias, const float* __restrict__ add,
-                                                             float* __restrict__ dst, ConvGeom g, int relu) {
+                                                             float* __restrict__ dst, ConvGeom g, int relu, int mode) {
     static_assert(KS == 1 || VEC, "several k-chunks per stage only with 16-byte gathers");
     constexpr int WM = BM / 64, WN = BN / 16;
     constexpr int KST = mma::KC * KS;                              // reduction indices per stage
@@ -98,13 +103,31 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
     constexpr int BS = DGRAD ? BN * LDA : KST * (BN + 4);
     constexpr int RPT = BM / 64;                                   // gathered rows per thread (VEC)
     constexpr int BV = KST * BN / 4 / THREADS > 0 ? KST * BN / 4 / THREADS : 1;     // 16-byte filter loads per thread and stage
-    extern __shared__ __attribute__((aligned(16))) float igemm_lds[];      // As[2][BM * LDA], then Bs[2][BS]
+    extern __shared__ __attribute__((aligned(16))) float igemm_lds[];      // As[2][BM * LDA], then Bs[2][BS], then the staged rows
     float (*As)[BM * LDA] = reinterpret_cast<float (*)[BM * LDA]>(igemm_lds);
     float (*Bs)[BS] = reinterpret_cast<float (*)[BS]>(igemm_lds + 2 * BM * LDA);
+    const float* Img = igemm_lds + 2 * BM * LDA + 2 * BS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long m0 = (long)blockIdx.x * BM;
+    const bool staged = !VEC && mode == IGEMM_STAGED;
     const int n0 = blockIdx.y * BN;
     const int taps = g.KH * g.KW;
+    // IGEMM_PARITY (d-input of a stride-2 layer, even H and W): the rows are ordered by the parity class (h % 2, w % 2) of
+    // the pixel, a workgroup's rows are of one class, and it walks only the taps that reach a dy pixel from that class
+    // (kh = (h + pad) mod 2, +2, ...): a quarter of the (pixel, tap) pairs, the others would multiply zeros.
+    const bool parity = DGRAD && mode == IGEMM_PARITY;
+    long m0 = (long)blockIdx.x * BM, Mrows = g.M;
+    ConvGeom gr = g;                                               // pixel grid the rows are decomposed on
+    int ph = 0, pw = 0, kh0 = 0, kw0 = 0, nkw = g.KW, ntaps = taps;
+    if (parity) {
+        const int tiles = gridDim.x >> 2, cls = blockIdx.x / tiles;
+        m0 = (long)(blockIdx.x - cls * tiles) * BM;
+        ph = cls >> 1; pw = cls & 1;
+        kh0 = (ph + g.pad) & 1; kw0 = (pw + g.pad) & 1;
+        nkw = (g.KW - kw0 + 1) >> 1;
+        ntaps = ((g.KH - kh0 + 1) >> 1) * nkw;
+        gr.OH = g.OH >> 1; gr.OW = g.OW >> 1;
+        Mrows = (long)g.N * gr.OH * gr.OW;
+    }
 
     floatx4 acc[WM][WN];
     mma::zero(acc);
@@ -117,22 +140,49 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
 #pragma unroll
         for (int e = 0; e < RPT; ++e) {
             const long m = m0 + (tid >> 2) + 64 * e;
-            rvalid[e] = m < g.M;
+            rvalid[e] = m < Mrows;
             const long mm = rvalid[e] ? m : 0;
-            row_pixel(g, mm, rn[e], roh[e], row_w[e]);
+            row_pixel(gr, mm, rn[e], roh[e], row_w[e]);
+            if (parity) { roh[e] = 2 * roh[e] + ph; row_w[e] = 2 * row_w[e] + pw; }
         }
     }
 
-    // element-wise gather (!VEC): thread t loads reduction index t % 16 of rows t / 16 + 16 e, the same rows in every chunk
+    // element-wise gather (!VEC): thread t loads reduction index t % 16 of rows t / 16 + 16 e, the same rows in every chunk.
+    // staged (forward, stride 1, the tile is whole rows of one image): the input rows the tile touches are copied to LDS
+    // with their zero padding once, in coalesced loads, and every chunk gathers from that copy; sow[] then holds the
+    // offset of the row's pixel in the copy.
     constexpr int EPT = BM * mma::KC / THREADS;
     int sn[VEC ? 1 : EPT], soh[VEC ? 1 : EPT], sow[VEC ? 1 : EPT];
+    const int twi = g.SW + 2 * g.pad;
     if constexpr (!VEC) {
+        if (staged) {
+            const unsigned per_image = (unsigned)(g.OH * g.OW);
+            const unsigned n = (unsigned)m0 / per_image;
+            const int oh0 = (int)(((unsigned)m0 - n * per_image) / (unsigned)g.OW);
+            const float* xin = src + (long)n * g.SH * g.SW * g.IC;
+            const int row_len = twi * g.IC, img_rows = BM / g.OW + g.KH - 1;
+            float* img = igemm_lds + 2 * BM * LDA + 2 * BS;
+            for (int idx = tid; idx < img_rows * row_len; idx += THREADS) {
+                const int r = idx / row_len, rest = idx - r * row_len;
+                const int sh = oh0 - g.pad + r, col = rest - g.pad * g.IC;       // col = sw * IC + ci
+                img[idx] = (sh >= 0 && sh < g.SH && col >= 0 && col < g.SW * g.IC) ? xin[((long)sh * g.SW) * g.IC + col] : 0.f;
+            }
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const long m = m0 + (tid >> 4) + 16 * e;
-            const long mm = m < g.M ? m : 0;
-            row_pixel(g, mm, sn[e], soh[e], sow[e]);
-            if (m >= g.M) sn[e] = -1;
+            for (int e = 0; e < EPT; ++e) {
+                const int pix = (tid >> 4) + 16 * e;
+                const int r = pix / g.OW, c = pix - r * g.OW;
+                sn[e] = 0; soh[e] = 0;
+                sow[e] = (r * twi + c) * g.IC;
+            }
+            __syncthreads();
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                const long m = m0 + (tid >> 4) + 16 * e;
+                const long mm = m < g.M ? m : 0;
+                row_pixel(g, mm, sn[e], soh[e], sow[e]);
+                if (m >= g.M) sn[e] = -1;
+            }
         }
     }
     float4 ra[VEC ? RPT * KS : 1];
@@ -141,13 +191,16 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
 #pragma unroll
     for (int e = 0; e < BV; ++e) rb[e] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int ktot = taps * g.IC;
-    const int nchunks = VEC ? taps * (g.IC / KST) : (ktot + mma::KC - 1) / mma::KC;
+    const int nchunks = VEC ? ntaps * (g.IC / KST) : (ktot + mma::KC - 1) / mma::KC;
 
     auto load = [&](int chunk) {
         if constexpr (VEC) {
             const int cpt = g.IC / KST;
-            const int tap = chunk / cpt, c0 = (chunk - tap * cpt) * KST;
-            const int kh = tap / g.KW, kw = tap - kh * g.KW;
+            const int tap_i = chunk / cpt, c0 = (chunk - tap_i * cpt) * KST;
+            int kh, kw;
+            if (parity) { const int ikh = tap_i / nkw; kh = kh0 + 2 * ikh; kw = kw0 + 2 * (tap_i - ikh * nkw); }
+            else { kh = tap_i / g.KW; kw = tap_i - kh * g.KW; }
+            const int tap = kh * g.KW + kw;
 #pragma unroll
             for (int e = 0; e < RPT; ++e) {
                 int sh, sw;
@@ -175,13 +228,19 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
             const int kk = k0 + (tid & 15);
             const int tap = kk / g.IC, ci = kk - tap * g.IC;
             const int kh = tap / g.KW, kw = tap - kh * g.KW;
+            if (staged) {
+                const int tap_off = (kh * twi + kw) * g.IC + ci;
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) {
-                float v = 0.f;
-                int sh, sw;
-                if (sn[e] >= 0 && kk < ktot && src_pixel<DGRAD>(g, soh[e], sow[e], kh, kw, sh, sw))
-                    v = src[(((long)sn[e] * g.SH + sh) * g.SW + sw) * g.IC + ci];
-                ras[e] = v;
+                for (int e = 0; e < EPT; ++e) ras[e] = kk < ktot ? Img[sow[e] + tap_off] : 0.f;
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) {
+                    float v = 0.f;
+                    int sh, sw;
+                    if (sn[e] >= 0 && kk < ktot && src_pixel<DGRAD>(g, soh[e], sow[e], kh, kw, sh, sw))
+                        v = src[(((long)sn[e] * g.SH + sh) * g.SW + sw) * g.IC + ci];
+                    ras[e] = v;
+                }
             }
             if (tid < 4 * BN) {               // forward only: filter rows are the flattened (tap, ci)
                 const int k = tid / (BN / 4), j4 = tid % (BN / 4);
@@ -246,8 +305,14 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
             const float bv = bias ? bias[col] : 0.f;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const long m = m0 + wave * (BM / 4) + 16 * wm + 4 * q + v;
-                if (m >= g.M) continue;
+                const long r = m0 + wave * (BM / 4) + 16 * wm + 4 * q + v;
+                if (r >= Mrows) continue;
+                long m = r;
+                if (parity) {
+                    int pn, phh, pww;
+                    row_pixel(gr, r, pn, phh, pww);
+                    m = ((long)pn * g.OH + 2 * phh + ph) * g.OW + 2 * pww + pw;
+                }
                 float x = acc[wm][wn][v] + bv;
                 if (add) x += add[m * g.OC + col];
                 if (relu) x = fmaxf(x, 0.f);
@@ -264,15 +329,22 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
 //   !VEC : rows are the flattened (tap, ci) index (first layer, Cin = 3), blockIdx.y = 0.
 // Layers wider than one tile (more than 16 * CI_T input or 16 * CO_T output channels) are cut into channel slices,
 // one per blockIdx.z: slice z covers input channels [ci0, ci0 + CIP) (VEC only) and output channels [co0, co0 + COP).
-template <int CI_T, int CO_T, bool VEC>
+//   IMG  : (!VEC, stride 1, a slice is whole rows of one image) the input rows a slice touches are staged in LDS with their
+//          zero padding first, in coalesced loads, and the (pixel, tap, ci) operand is gathered from that copy through
+//          offsets each thread works out once: the element-wise gather from global memory costs far more than the MFMAs.
+constexpr int WGRAD_IMG_MAX = 2048;                 // floats of the staged input rows
+template <int CI_T, int CO_T, bool VEC, bool IMG = false>
 __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy,
                                                              float* __restrict__ partial, ConvGeom g, int stages, int rows_total) {
+    static_assert(!(VEC && IMG), "staged rows serve the element-wise gather only");
     constexpr int CIP = 16 * CI_T, COP = 16 * CO_T;
     constexpr int LDA = CIP + 4, LDB = COP + 4;
     constexpr int PIX = 64;
+    static_assert(CIP * COP <= PIX * LDA, "the cross-wavefront sum reuses the operand tile");
     __shared__ __attribute__((aligned(16))) float Xs[PIX * LDA];
     __shared__ __attribute__((aligned(16))) float Ds[PIX * LDB];
-    __shared__ __attribute__((aligned(16))) float Red[CIP * COP];
+    __shared__ __attribute__((aligned(16))) float Img[IMG ? WGRAD_IMG_MAX : 4];
+    float* Red = Xs;                                                // used after the last slice has been consumed
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tap = blockIdx.y;
     const int kh = tap / g.KW, kw = tap - kh * g.KW;
@@ -283,6 +355,82 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_kernel(const float* __rest
     floatx4 acc[CI_T][CO_T];
     mma::zero(acc);
 
+    // IMG: the staged copy holds rows [oh0 - pad, oh0 + PIX / OW + KH - 1 - pad) of the image, TWI = SW + 2 pad columns each
+    constexpr int EPT = PIX * CIP / THREADS;
+    int img_off[IMG ? EPT : 1];
+    const int twi = g.SW + 2 * g.pad, row_len = twi * g.IC, img_rows = PIX / g.OW + g.KH - 1;
+    if constexpr (IMG) {
+        // offset of (tap, ci) within the copy, one division pair per reduction index; OW is a power of two here
+        int* tap_off = reinterpret_cast<int*>(Ds);
+        if (tid < CIP) {
+            const int t2 = tid / g.IC, ci = tid - t2 * g.IC;
+            const int kh2 = t2 / g.KW, kw2 = t2 - kh2 * g.KW;
+            tap_off[tid] = tid < rows_total ? (kh2 * twi + kw2) * g.IC + ci : -1;
+        }
+        __syncthreads();
+        const int lw = __ffs(g.OW) - 1;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int idx = tid + e * THREADS;
+            const int pix = idx / CIP, kk = idx % CIP;
+            const int t = tap_off[kk];
+            img_off[e] = t >= 0 ? t + ((pix >> lw) * twi + (pix & (g.OW - 1))) * g.IC : -1;
+        }
+    }
+
+    if constexpr (IMG) {
+        // global -> registers -> LDS, the next slice's loads in flight while the matrix cores work on the current one
+        constexpr int IV = WGRAD_IMG_MAX / THREADS, DV = PIX * (COP / 4) / THREADS;
+        static_assert(DV >= 1 && THREADS % (COP / 4) == 0, "dy rows per thread");
+        int img_rc[IV];                                             // (row << 16 | position in the row) of the thread's staged elements
+#pragma unroll
+        for (int e = 0; e < IV; ++e) {
+            const int idx = tid + e * THREADS;
+            const int r = idx / row_len;
+            img_rc[e] = idx < img_rows * row_len ? (r << 16) | (idx - r * row_len) : -1;
+        }
+        float ri[IV];
+        float4 rd[DV];
+        auto fetch = [&](long p0) {
+            const unsigned per_image = (unsigned)(g.OH * g.OW);
+            const unsigned n = (unsigned)p0 / per_image;
+            const int oh0 = (int)(((unsigned)p0 - n * per_image) / (unsigned)g.OW);
+            const float* xin = x + (long)n * g.SH * g.SW * g.IC;
+#pragma unroll
+            for (int e = 0; e < IV; ++e) {
+                const int sh = oh0 - g.pad + (img_rc[e] >> 16), col = (img_rc[e] & 0xffff) - g.pad * g.IC;     // col = sw * IC + ci
+                ri[e] = (img_rc[e] >= 0 && sh >= 0 && sh < g.SH && col >= 0 && col < g.SW * g.IC) ? xin[sh * g.SW * g.IC + col] : 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < DV; ++e) {
+                const int idx = tid + e * THREADS;
+                rd[e] = *reinterpret_cast<const float4*>(dy + (p0 + idx / (COP / 4)) * g.OC + co0 + 4 * (idx % (COP / 4)));   // M is a multiple of PIX here
+            }
+        };
+        int nst = stages;
+        if (p_begin + (long)nst * PIX > g.M) nst = p_begin < g.M ? (int)((g.M - p_begin) / PIX) : 0;
+        if (nst > 0) fetch(p_begin);
+        for (int st = 0; st < nst; ++st) {
+            __syncthreads();                                        // previous slice fully consumed
+#pragma unroll
+            for (int e = 0; e < IV; ++e)
+                if (img_rc[e] >= 0) Img[tid + e * THREADS] = ri[e];
+#pragma unroll
+            for (int e = 0; e < DV; ++e) {
+                const int idx = tid + e * THREADS;
+                *reinterpret_cast<float4*>(&Ds[(idx / (COP / 4)) * LDB + 4 * (idx % (COP / 4))]) = rd[e];
+            }
+            __syncthreads();                                        // staged rows complete
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                const int idx = tid + e * THREADS;
+                Xs[(idx / CIP) * LDA + idx % CIP] = img_off[e] >= 0 ? Img[img_off[e]] : 0.f;
+            }
+            if (st + 1 < nst) fetch(p_begin + (long)(st + 1) * PIX);
+            __syncthreads();
+            mma::chunk16<CI_T, CO_T, true, false>(Xs + 16 * wave * LDA, LDA, Ds + 16 * wave * LDB, LDB, 0, 0, acc, lane);
+        }
+    } else
     for (int st = 0; st < stages; ++st) {
         const long p0 = p_begin + (long)st * PIX;
         if (p0 >= g.M) break;
@@ -388,30 +536,36 @@ __global__ __launch_bounds__(THREADS) void conv_wgrad_tile_kernel(const float* _
     floatx4 acc[TM][TN];
     mma::zero(acc);
     float4 rx[XV], rd[DV];
-    auto load = [&](int st) {
-        const long p0 = p_begin + (long)st * PIX;
+    // The pixels a thread gathers move on by PIX from slice to slice: (image, row, column) are decomposed once and then
+    // stepped with carries, since a division per gathered row and slice costs as many cycles as the slice's MFMAs.
+    int pn[XV], poh[XV], pw[XV];
+#pragma unroll
+    for (int e = 0; e < XV; ++e) row_pixel(g, p_begin + (tid + e * THREADS) / (CIP / 4), pn[e], poh[e], pw[e]);
+    int step_n, step_h, step_w;
+    row_pixel(g, PIX, step_n, step_h, step_w);
+    long dy_row = p_begin + tid / (COP / 4);                       // first of the thread's dy rows; the others follow at THREADS / (COP / 4)
+    auto load = [&](int) {
 #pragma unroll
         for (int e = 0; e < XV; ++e) {
-            const int idx = tid + e * THREADS;
-            const int pix = idx / (CIP / 4), c4 = idx % (CIP / 4);
-            const long m = p0 + pix;
+            const int c4 = (tid + e * THREADS) % (CIP / 4);
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (m < g.M) {
-                int n, oh, ow;
-                    row_pixel(g, m, n, oh, ow);
-                int sh, sw;
-                if (src_pixel<false>(g, oh, ow, kh, kw, sh, sw))
-                    v = *reinterpret_cast<const float4*>(x + (((long)n * g.SH + sh) * g.SW + sw) * g.IC + 4 * c4);
-            }
+            int sh, sw;
+            if (pn[e] < g.N && src_pixel<false>(g, poh[e], pw[e], kh, kw, sh, sw))
+                v = *reinterpret_cast<const float4*>(x + (long)((pn[e] * g.SH + sh) * g.SW + sw) * g.IC + 4 * c4);
             rx[e] = v;
+            pw[e] += step_w;
+            if (pw[e] >= g.OW) { pw[e] -= g.OW; ++poh[e]; }
+            poh[e] += step_h;
+            if (poh[e] >= g.OH) { poh[e] -= g.OH; ++pn[e]; }
+            pn[e] += step_n;
         }
 #pragma unroll
         for (int e = 0; e < DV; ++e) {
-            const int idx = tid + e * THREADS;
-            const int pix = idx / (COP / 4), c4 = idx % (COP / 4);
-            const long m = p0 + pix;
+            const long m = dy_row + e * (THREADS / (COP / 4));
+            const int c4 = tid % (COP / 4);
             rd[e] = m < g.M ? *reinterpret_cast<const float4*>(dy + m * g.OC + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
+        dy_row += PIX;
     };
     auto store = [&](int buf) {
 #pragma unroll
@@ -494,19 +648,32 @@ bool geom(ConvGeom& g, int N, int H, int W, int Cin, int Cout, int KH, int KW, i
     g.OH = (H + 2 * pad - KH) / stride + 1;
     g.OW = (W + 2 * pad - KW) / stride + 1;
     g.M = (long)N * g.OH * g.OW;
-    return g.M < (1L << 31);
+    return g.M < (1L << 31) && (long)N * H * W < (1L << 31);      // pixel indices are 32-bit in the kernels
 }
 
-int wgrad_stages(const ConvGeom& g, int grid_y) {
-    // about 288 workgroups; four times as many where the gather is scalar (Cin not a multiple of 16: the loads of a
-    // slice are many and narrow, so more of them have to be in flight)
-    long s = g.M * grid_y / (64L * (g.IC % 16 ? 1152L : 288L));
+// d-filter, element-wise gather: 64-pixel slices are whole rows of one image and the rows they touch fit the staged copy
+bool wgrad_staged(const ConvGeom& g) {
+    return g.IC % 16 != 0 && g.stride == 1 && g.OW <= 64 && 64 % g.OW == 0 && ((long)g.OH * g.OW) % 64 == 0 &&
+           (long)(64 / g.OW + g.KH - 1) * (g.SW + 2 * g.pad) * g.IC <= WGRAD_IMG_MAX;
+}
+
+int wgrad_stages(const ConvGeom& g, int grid_y, bool staged) {
+    // about 1152 workgroups (a slice's loads are not overlapped with its MFMAs in the plain kernel, so several workgroups
+    // per compute unit have to hide them), half as many with the staged gather, whose set-up per workgroup costs more
+    long s = g.M * grid_y / (64L * (staged ? 576L : 1152L));
     if (s < 1) s = 1;
-    if (s > 16) s = 16;
+    if (s > 16) {                      // large problems: about two workgroups per compute unit, however many slices that takes
+        long chunks = 512L / grid_y;
+        if (chunks < 1) chunks = 1;
+        const long slices = (g.M + 63) / 64;
+        s = (slices + chunks - 1) / chunks;
+        if (s < 16) s = 16;
+    }
     return (int)s;
 }
 
-// LDS of an instantiation (floats), as laid out in the kernel
+
+// LDS of an instantiation's operand tiles (bytes), as laid out in the kernel
 template <int BM, int BN, bool DGRAD, int KS>
 constexpr size_t igemm_lds_bytes() {
     constexpr int KST = mma::KC * KS, LDA = KST + 4;
@@ -515,17 +682,21 @@ constexpr size_t igemm_lds_bytes() {
 
 template <int BM, int BN, bool DGRAD, bool VEC, int KS>
 int igemm_launch(dim3 grid, hipStream_t s, const float* src, const float* w, const float* bias, const float* add, float* dst,
-                 const ConvGeom& g, int relu) {
-    constexpr size_t bytes = igemm_lds_bytes<BM, BN, DGRAD, KS>();
+                 const ConvGeom& g, int relu, bool parity) {
+    // staged gather: forward, element-wise, stride 1, tiles of whole rows of one image, the rows they touch within the LDS budget
+    const bool staged = !VEC && !DGRAD && g.stride == 1 && g.OW <= BM && BM % g.OW == 0 && ((long)g.OH * g.OW) % BM == 0 &&
+                        (long)(BM / g.OW + g.KH - 1) * (g.SW + 2 * g.pad) * g.IC <= IGEMM_IMG_MAX;
+    const size_t bytes = igemm_lds_bytes<BM, BN, DGRAD, KS>() + (staged ? sizeof(float) * IGEMM_IMG_MAX : 0);
     auto kern = conv_igemm_kernel<BM, BN, DGRAD, VEC, KS>;
     static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
     if (!attr_set) {
-        if (bytes > 48 * 1024 &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+        constexpr size_t most = igemm_lds_bytes<BM, BN, DGRAD, KS>() + (VEC ? 0 : sizeof(float) * IGEMM_IMG_MAX);
+        if (most > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)most) != hipSuccess)
             return -1;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(THREADS), bytes, s, src, w, bias, add, dst, g, relu);
+    hipLaunchKernelGGL(kern, grid, dim3(THREADS), bytes, s, src, w, bias, add, dst, g, relu, staged ? IGEMM_STAGED : parity ? IGEMM_PARITY : 0);
     return 0;
 }
 
@@ -536,9 +707,11 @@ int launch_igemm(hipStream_t s, const float* src, const float* w, const float* b
     if (!bn) return -1;
     // small problems take 64-pixel tiles so that the grid still covers the chip
     const bool small = g.M < 128L * 512;
-    dim3 grid(ceil_div(g.M, small ? 64 : 128), g.OC / bn);
-#define GO(BM, BN) do { if (igemm_launch<BM, BN, DGRAD, VEC, 1>(grid, s, src, w, bias, add, dst, g, relu)) return -1; } while (0)
-#define GOK(BM, BN, KS) do { if (igemm_launch<BM, BN, DGRAD, VEC, KS>(grid, s, src, w, bias, add, dst, g, relu)) return -1; } while (0)
+    // d-input of a stride-2 layer on an even pixel grid: four parity classes of rows, each with its own tiles
+    const bool parity = DGRAD && VEC && g.stride == 2 && g.OH % 2 == 0 && g.OW % 2 == 0;
+    dim3 grid(parity ? 4 * ceil_div(g.M / 4, small ? 64 : 128) : ceil_div(g.M, small ? 64 : 128), g.OC / bn);
+#define GO(BM, BN) do { if (igemm_launch<BM, BN, DGRAD, VEC, 1>(grid, s, src, w, bias, add, dst, g, relu, parity)) return -1; } while (0)
+#define GOK(BM, BN, KS) do { if (igemm_launch<BM, BN, DGRAD, VEC, KS>(grid, s, src, w, bias, add, dst, g, relu, parity)) return -1; } while (0)
     if constexpr (VEC) {
         if (bn == 64 && g.IC % 64 == 0 && small) {      // wide layers: several k-chunks per stage
             GOK(64, 64, 4);
@@ -615,7 +788,7 @@ extern "C" size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, 
     ConvGeom g;
     if (!geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return 0;
     const int gy = (Cin % 16 == 0) ? KH * KW : 1;
-    const int stages = wgrad_stages(g, gy);
+    const int stages = wgrad_stages(g, gy, wgrad_staged(g));
     long chunks = ceil_div(g.M, 64L * stages);
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
         const long parts = wgrad3x3_tiled_parts(N, H, Cin);
@@ -638,8 +811,10 @@ static int wgrad_stage1(hipStream_t s, const float* x, const float* dy, float* s
             return wgrad3x3_tiled(s, x, dy, scratch, N, H, Cin, tj);
         }
     }
+    // element-wise layers whose 64-pixel slices are whole rows of one image gather from a staged copy of those rows
+    const bool img = wgrad_staged(g);
     const int gy = vec ? KH * KW : 1;
-    const int stages = wgrad_stages(g, gy);
+    const int stages = wgrad_stages(g, gy, img);
     const int chunks = ceil_div(g.M, 64L * stages);
     *chunks_out = chunks;
     dim3 grid(chunks, gy);
@@ -647,7 +822,8 @@ static int wgrad_stage1(hipStream_t s, const float* x, const float* dy, float* s
     const int cop = Cout % 64 == 0 ? 64 : Cout % 32 == 0 ? 32 : 16;
     const int cip = !vec ? 0 : Cin % 64 == 0 ? 64 : Cin % 32 == 0 ? 32 : 16;
     const bool sliced = Cout > 64 || (vec && Cin > 64);
-#define GO(CI, CO, V) hipLaunchKernelGGL((conv_wgrad_kernel<CI, CO, V>), grid, dim3(THREADS), 0, s, x, dy, scratch, g, stages, rows_total)
+#define GO(CI, CO, V) do { if (!V && img) hipLaunchKernelGGL((conv_wgrad_kernel<CI, CO, V, !V>), grid, dim3(THREADS), 0, s, x, dy, scratch, g, stages, rows_total); \
+                           else hipLaunchKernelGGL((conv_wgrad_kernel<CI, CO, V, false>), grid, dim3(THREADS), 0, s, x, dy, scratch, g, stages, rows_total); } while (0)
 #define GO_CO(CI, V) do { if (cop == 16) GO(CI, 1, V); else if (cop == 32) GO(CI, 2, V); else GO(CI, 4, V); } while (0)
     if (sliced) {
         if (tj.blocks) return -1;

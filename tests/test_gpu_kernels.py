@@ -228,6 +228,14 @@ CONV_CASES = [  # N, H, Cin, Cout, k, stride, pad, bias+relu
     (3, 9, 96, 80, 3, 2, 1, False),
     (2, 7, 128, 192, 5, 1, 2, True),
     (2, 12, 3, 96, 5, 1, 2, True),
+    (3, 16, 3, 32, 3, 1, 1, False),          # few input channels, tiles of whole image rows: the gather reads staged rows
+    (5, 8, 3, 16, 5, 1, 2, True),
+    (2, 64, 3, 16, 3, 1, 1, False),
+    (3, 32, 5, 32, 3, 1, 0, True),           # no padding: 30 columns, tiles are not whole rows (gather from global memory)
+    (128, 32, 3, 64, 5, 1, 2, True),         # first layer of the AlexNet-style net, batch 128
+    (2, 12, 16, 32, 5, 2, 2, False),         # stride 2 on an even grid: the d-input kernel works by parity class of the pixel
+    (3, 8, 32, 64, 1, 2, 0, False),          # 1x1 stride 2: three of the four classes receive no gradient at all
+    (2, 10, 16, 16, 4, 2, 1, False),         # even filter size
     (128, 32, 16, 16, 3, 1, 1, False),       # benchmark shapes, batch 128
     (128, 16, 32, 32, 3, 1, 1, False),
     (128, 8, 64, 64, 3, 1, 1, False),
