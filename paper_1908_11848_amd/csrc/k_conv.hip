@@ -283,7 +283,7 @@ __global__ __launch_bounds__(THREADS) void conv_igemm_kernel(const float* __rest
         }
     };
 
-    load(0);
+    if (nchunks > 0) load(0);          // a parity class that no tap reaches has no chunk at all: its rows are zero (+ add)
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
         store(buf);
@@ -657,19 +657,29 @@ bool wgrad_staged(const ConvGeom& g) {
            (long)(64 / g.OW + g.KH - 1) * (g.SW + 2 * g.pad) * g.IC <= WGRAD_IMG_MAX;
 }
 
-int wgrad_stages(const ConvGeom& g, int grid_y, bool staged) {
-    // about 1152 workgroups (a slice's loads are not overlapped with its MFMAs in the plain kernel, so several workgroups
-    // per compute unit have to hide them), half as many with the staged gather, whose set-up per workgroup costs more
-    long s = g.M * grid_y / (64L * (staged ? 576L : 1152L));
-    if (s < 1) s = 1;
-    if (s > 16) {                      // large problems: about two workgroups per compute unit, however many slices that takes
+// d-filter: layers of at least four 16x16 tiles per tap go to conv_wgrad_tile_kernel
+bool wgrad_tiled(const ConvGeom& g) {
+    const int Cin = g.IC, Cout = g.OC;
+    return (Cout == 64 && (Cin == 16 || Cin == 32 || Cin == 64)) || (Cout == 32 && (Cin == 32 || Cin == 64));     // its instantiations
+}
+
+// Slices of 64 pixels per workgroup.
+int wgrad_stages(const ConvGeom& g, int grid_y) {
+    const long slices = (g.M + 63) / 64;
+    long s;
+    if (wgrad_tiled(g)) {
+        // the tile kernel overlaps a slice's loads with the previous slice's MFMAs and LDS lets two workgroups share a CU:
+        // at most one round of 512 workgroups, however many slices that takes (a second, partly filled round costs a fifth)
         long chunks = 512L / grid_y;
         if (chunks < 1) chunks = 1;
-        const long slices = (g.M + 63) / 64;
         s = (slices + chunks - 1) / chunks;
-        if (s < 16) s = 16;
+    } else {
+        // the plain kernel does not overlap them, so several workgroups per compute unit have to: about 1152 workgroups,
+        // half as many with the staged gather, whose set-up per workgroup costs more
+        s = slices * grid_y / (wgrad_staged(g) ? 576L : 1152L);
+        if (s > 16) s = 16;
     }
-    return (int)s;
+    return (int)(s < 1 ? 1 : s);
 }
 
 
@@ -788,7 +798,7 @@ extern "C" size_t dsspk_conv_wgrad_scratch_floats(int N, int H, int W, int Cin, 
     ConvGeom g;
     if (!geom(g, N, H, W, Cin, Cout, KH, KW, stride, pad)) return 0;
     const int gy = (Cin % 16 == 0) ? KH * KW : 1;
-    const int stages = wgrad_stages(g, gy, wgrad_staged(g));
+    const int stages = wgrad_stages(g, gy);
     long chunks = ceil_div(g.M, 64L * stages);
     if (KH == 3 && KW == 3 && stride == 1 && pad == 1 && Cin == Cout && H == W) {
         const long parts = wgrad3x3_tiled_parts(N, H, Cin);
@@ -814,14 +824,14 @@ static int wgrad_stage1(hipStream_t s, const float* x, const float* dy, float* s
     // element-wise layers whose 64-pixel slices are whole rows of one image gather from a staged copy of those rows
     const bool img = wgrad_staged(g);
     const int gy = vec ? KH * KW : 1;
-    const int stages = wgrad_stages(g, gy, img);
+    const int stages = wgrad_stages(g, gy);
     const int chunks = ceil_div(g.M, 64L * stages);
     *chunks_out = chunks;
     dim3 grid(chunks, gy);
     // channel slices of the widest tile that divides the layer: 64, 32 or 16 channels
     const int cop = Cout % 64 == 0 ? 64 : Cout % 32 == 0 ? 32 : 16;
     const int cip = !vec ? 0 : Cin % 64 == 0 ? 64 : Cin % 32 == 0 ? 32 : 16;
-    const bool sliced = Cout > 64 || (vec && Cin > 64);
+    const bool sliced = !wgrad_tiled(g) && (Cout > cop || (vec && Cin > cip));
 #define GO(CI, CO, V) do { if (!V && img) hipLaunchKernelGGL((conv_wgrad_kernel<CI, CO, V, !V>), grid, dim3(THREADS), 0, s, x, dy, scratch, g, stages, rows_total); \
                            else hipLaunchKernelGGL((conv_wgrad_kernel<CI, CO, V, false>), grid, dim3(THREADS), 0, s, x, dy, scratch, g, stages, rows_total); } while (0)
 #define GO_CO(CI, V) do { if (cop == 16) GO(CI, 1, V); else if (cop == 32) GO(CI, 2, V); else GO(CI, 4, V); } while (0)
@@ -829,7 +839,7 @@ static int wgrad_stage1(hipStream_t s, const float* x, const float* dy, float* s
         if (tj.blocks) return -1;
         grid.z = (unsigned)((Cout / cop) * (vec ? Cin / cip : 1));
     }
-    if (!sliced && vec && (Cin / 16) * (Cout / 16) >= 4 && Cout >= 32 && (Cin == 16 || Cin == 32 || Cin == 64)) {
+    if (wgrad_tiled(g)) {
         if (Cin == 64 && Cout == 64) return launch_wgrad_tile<4, 4>(s, x, dy, scratch, g, stages, grid, tj);
         if (Cin == 32 && Cout == 64) return launch_wgrad_tile<2, 4>(s, x, dy, scratch, g, stages, grid, tj);
         if (Cin == 32 && Cout == 32) return launch_wgrad_tile<2, 2>(s, x, dy, scratch, g, stages, grid, tj);

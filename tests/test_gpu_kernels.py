@@ -236,6 +236,9 @@ CONV_CASES = [  # N, H, Cin, Cout, k, stride, pad, bias+relu
     (2, 12, 16, 32, 5, 2, 2, False),         # stride 2 on an even grid: the d-input kernel works by parity class of the pixel
     (3, 8, 32, 64, 1, 2, 0, False),          # 1x1 stride 2: three of the four classes receive no gradient at all
     (2, 10, 16, 16, 4, 2, 1, False),         # even filter size
+    (2, 8, 32, 48, 3, 1, 1, False),          # widths between the d-filter tile kernel's instantiations
+    (2, 8, 16, 64, 3, 1, 1, True),
+    (2, 8, 64, 32, 3, 1, 1, False),
     (128, 32, 16, 16, 3, 1, 1, False),       # benchmark shapes, batch 128
     (128, 16, 32, 32, 3, 1, 1, False),
     (128, 8, 64, 64, 3, 1, 1, False),
