@@ -246,7 +246,23 @@ CONV_CASES = [  # N, H, Cin, Cout, k, stride, pad, bias+relu
 ]
 
 
-@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "x".join(map(str, c)))
+def random_conv_cases(seed=20, count=48):
+    """Seeded shapes across the generic kernels' paths: few / 16-multiple input channels, widths between the tile sizes,
+    even and odd pixel grids, strides 1-3, filter sizes 1-5, with and without padding."""
+    g = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        N, H = int(g.integers(1, 4)), int(g.choice([4, 6, 7, 8, 9, 12, 16]))
+        Cin = int(g.choice([1, 3, 5, 16, 32, 48, 64, 80, 96]))
+        Cout = int(g.choice([16, 32, 48, 64, 80, 96, 128]))
+        k, s, p = int(g.integers(1, 6)), int(g.integers(1, 4)), int(g.integers(0, 3))
+        if H + 2 * p < k or (Cin % 16 and k * k * Cin > 80):      # the element-wise d-filter kernel holds 80 (tap, ci) rows
+            continue
+        cases.append((N, H, Cin, Cout, k, s, p, bool(g.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("case", CONV_CASES + random_conv_cases(), ids=lambda c: "x".join(map(str, c)))
 def test_conv_forward_dgrad_wgrad(oracle_nn, case):
     N, H, Cin, Cout, k, s, p, br = case
     g = np.random.default_rng(hash(case) % (1 << 31))
