@@ -136,17 +136,30 @@ __global__ __launch_bounds__(THREADS) void maxpool_bwd4_kernel(const float4* __r
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
         const int ho_lo = hi >= 2 ? (hi - 1) / 2 : 0, ho_hi = min(Ho - 1, hi / 2);
         const int wo_lo = wi >= 2 ? (wi - 1) / 2 : 0, wo_hi = min(Wo - 1, wi / 2);
-        for (int ho = ho_lo; ho <= ho_hi; ++ho)           // same window order as the scalar kernel: sums are identical
-            for (int wo = wo_lo; wo <= wo_hi; ++wo) {
-                const size_t o = ((size_t)(n * Ho + ho) * Wo + wo) * C4 + c;
-                const unsigned char want = (unsigned char)((hi - 2 * ho) * 3 + (wi - 2 * wo));
-                const uchar4 ch = arg[o];
-                const float4 g = dy[o];
-                if (ch.x == want) s.x += g.x;
-                if (ch.y == want) s.y += g.y;
-                if (ch.z == want) s.z += g.z;
-                if (ch.w == want) s.w += g.w;
-            }
+        // A pixel lies in at most 2 x 2 windows (3x3, stride 2).  All four candidates are fetched at once (index clamped,
+        // contribution dropped where the window does not exist) and added in the scalar kernel's window order, so the sums
+        // are identical; one window after the other, each fetch would wait for the one before.
+        uchar4 ch[4];
+        float4 g[4];
+        bool use[4];
+        unsigned char want[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int ho = ho_lo + (k >> 1), wo = wo_lo + (k & 1);
+            use[k] = ho <= ho_hi && wo <= wo_hi;
+            const int hc = min(ho, Ho - 1), wc = min(wo, Wo - 1);
+            const size_t o = ((size_t)(n * Ho + hc) * Wo + wc) * C4 + c;
+            want[k] = (unsigned char)((hi - 2 * ho) * 3 + (wi - 2 * wo));
+            ch[k] = arg[o];
+            g[k] = dy[o];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (use[k] && ch[k].x == want[k]) s.x += g[k].x;
+            if (use[k] && ch[k].y == want[k]) s.y += g[k].y;
+            if (use[k] && ch[k].z == want[k]) s.z += g[k].z;
+            if (use[k] && ch[k].w == want[k]) s.w += g[k].w;
+        }
         if constexpr (MASK) {
             const float4 av = a[i];
             s.x = av.x > 0.f ? s.x : 0.f; s.y = av.y > 0.f ? s.y : 0.f;
